@@ -1,0 +1,102 @@
+"""CPU oracle for the DCNv4 spatial-aggregation operator.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around oracle/dcnv4_oracle.c (plain double-precision loops that
+write out Eq. 1-2 of the paper and their chain-rule gradients).  Only the tests, the
+smoke check and the benchmark's CPU-baseline leg may import this package; the
+product package never does, and this package imports nothing from the product.
+
+Arrays are numpy, any float dtype on input (widened exactly to float64), float64 out:
+  x [N,H,W,C]   offset [N,Ho,Wo,G,K,2] ([...,0] along width, [...,1] along height)
+  mask [N,Ho,Wo,G,K]   y / grad_y [N,Ho,Wo,C]
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = ctypes.CDLL(path)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ints = [ctypes.c_int] * 13
+        lib.dcnv4_oracle_forward.argtypes = [dp, dp, dp, dp] + ints + [ctypes.c_double]
+        lib.dcnv4_oracle_forward.restype = ctypes.c_int
+        lib.dcnv4_oracle_backward.argtypes = [dp] * 7 + ints + [ctypes.c_double]
+        lib.dcnv4_oracle_backward.restype = ctypes.c_int
+        lib.dcnv4_oracle_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Number of host threads the oracle's loops run on."""
+    return int(_load().dcnv4_oracle_threads())
+
+
+def _pair(v):
+    return (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
+
+
+def output_hw(H, W, kernel=3, stride=1, pad=1, dilation=1):
+    (kh, kw), (sh, sw), (ph, pw), (dh, dw) = map(_pair, (kernel, stride, pad, dilation))
+    Ho = (H + 2 * ph - dh * (kh - 1) - 1) // sh + 1
+    Wo = (W + 2 * pw - dw * (kw - 1) - 1) // sw + 1
+    return Ho, Wo
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _geometry(x, offset, mask, kernel, stride, pad, dilation):
+    (kh, kw), (sh, sw), (ph, pw), (dh, dw) = map(_pair, (kernel, stride, pad, dilation))
+    N, H, W, C = x.shape
+    Ho, Wo = output_hw(H, W, kernel, stride, pad, dilation)
+    K = kh * kw
+    if mask.ndim != 5 or mask.shape[:3] != (N, Ho, Wo) or mask.shape[4] != K:
+        raise ValueError(f"mask shape {mask.shape} does not match [N={N},Ho={Ho},Wo={Wo},G,K={K}]")
+    G = mask.shape[3]
+    if offset.shape != (N, Ho, Wo, G, K, 2):
+        raise ValueError(f"offset shape {offset.shape} != {(N, Ho, Wo, G, K, 2)}")
+    if C % G:
+        raise ValueError("C must be a multiple of G")
+    return (N, H, W, G, C // G, kh, kw, sh, sw, ph, pw, dh, dw), (Ho, Wo)
+
+
+def forward(x, offset, mask, kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0):
+    """y = sum_k m_k * bilinear(x_g, p0 + p_k + offset_scale * dp_k)   (Eq. 1-2, no softmax)."""
+    x, offset, mask = _f64(x), _f64(offset), _f64(mask)
+    geo, (Ho, Wo) = _geometry(x, offset, mask, kernel, stride, pad, dilation)
+    y = np.empty((x.shape[0], Ho, Wo, x.shape[3]), dtype=np.float64)
+    rc = _load().dcnv4_oracle_forward(_ptr(x), _ptr(offset), _ptr(mask), _ptr(y), *geo,
+                                      float(offset_scale))
+    if rc:
+        raise ValueError("dcnv4_oracle_forward: bad geometry")
+    return y
+
+
+def backward(x, offset, mask, grad_y, kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0):
+    """Chain-rule gradients of forward(): returns (grad_x, grad_offset, grad_mask)."""
+    x, offset, mask, grad_y = _f64(x), _f64(offset), _f64(mask), _f64(grad_y)
+    geo, (Ho, Wo) = _geometry(x, offset, mask, kernel, stride, pad, dilation)
+    if grad_y.shape != (x.shape[0], Ho, Wo, x.shape[3]):
+        raise ValueError("grad_y shape mismatch")
+    gx = np.empty_like(x)
+    go = np.empty_like(offset)
+    gm = np.empty_like(mask)
+    rc = _load().dcnv4_oracle_backward(_ptr(x), _ptr(offset), _ptr(mask), _ptr(grad_y),
+                                       _ptr(gx), _ptr(go), _ptr(gm), *geo, float(offset_scale))
+    if rc:
+        raise ValueError("dcnv4_oracle_backward: bad geometry")
+    return gx, go, gm

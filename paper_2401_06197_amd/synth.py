@@ -1,0 +1,81 @@
+"""Seeded synthetic inputs for the DCNv4 operator (shapes of the benchmark configs).
+
+This module holds no arithmetic of the operator itself: it only draws random tensors
+of the right shapes on the CPU, so that the HIP path and the CPU checker can be fed
+identical values.  Recipe (one torch CPU generator per call, draw order fixed):
+  x ~ N(0,1) [N,H,W,C];  offset = sigma * N(0,1) [N,Ho,Wo,G,K,2];  mask ~ N(0,1)
+  [N,Ho,Wo,G,K] (unnormalised);  grad_y ~ N(0,1) [N,Ho,Wo,C];  then a Bernoulli(1/8)
+  draw per (n,h,w,g,k) selects offset pairs that are rounded to whole numbers, so some
+  samples land exactly on pixel centres.  For an fp16 run every tensor is rounded to
+  fp16 once, here, so both consumers see the same already-rounded values.
+These stand in for InternImage / FlashInternImage stage feature maps at 224x224 input
+(4x..32x downsampling) and for a detection-sized feature map; no dataset is involved.
+"""
+from dataclasses import dataclass, asdict
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class Config:
+    name: str
+    N: int
+    H: int
+    W: int
+    C: int
+    G: int
+    sigma: float = 2.0          # std of the raw offsets, in pixels
+    kernel: int = 3
+    stride: int = 1
+    pad: int = 1
+    dilation: int = 1
+    offset_scale: float = 1.0
+
+    @property
+    def Cg(self):
+        return self.C // self.G
+
+    @property
+    def out_hw(self):
+        k, s, p, d = self.kernel, self.stride, self.pad, self.dilation
+        return ((self.H + 2 * p - d * (k - 1) - 1) // s + 1,
+                (self.W + 2 * p - d * (k - 1) - 1) // s + 1)
+
+    def with_(self, **kw):
+        d = asdict(self)
+        d.update(kw)
+        return Config(**d)
+
+
+CONFIGS = {
+    # tiny forward+backward case
+    "c1": Config("c1", N=1, H=14, W=14, C=64, G=4),
+    # InternImage stage-1 shape (forward fp32/fp16; with grad_y it is the training-step case)
+    "c2": Config("c2", N=64, H=56, W=56, C=128, G=8),
+    # stage sweep
+    "c3_28": Config("c3_28", N=64, H=28, W=28, C=256, G=16),
+    "c3_14": Config("c3_14", N=64, H=14, W=14, C=512, G=32),
+    "c3_7": Config("c3_7", N=64, H=7, W=7, C=1024, G=64),
+    # dense-prediction high-resolution shape, wider offsets
+    "c4": Config("c4", N=2, H=200, W=336, C=256, G=16, sigma=4.0),
+}
+CONFIGS["c5"] = CONFIGS["c2"].with_(name="c5")
+
+
+def make_inputs(cfg: Config, dtype: str = "f32", seed: int = 0, integer_fraction: float = 0.125):
+    """Return dict(x, offset, mask, grad_y) of numpy arrays in `dtype` ('f32' or 'f16')."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    K = cfg.kernel * cfg.kernel
+    Ho, Wo = cfg.out_hw
+    x = torch.randn((cfg.N, cfg.H, cfg.W, cfg.C), generator=gen, dtype=torch.float32)
+    off = torch.randn((cfg.N, Ho, Wo, cfg.G, K, 2), generator=gen, dtype=torch.float32) * cfg.sigma
+    m = torch.randn((cfg.N, Ho, Wo, cfg.G, K), generator=gen, dtype=torch.float32)
+    gy = torch.randn((cfg.N, Ho, Wo, cfg.C), generator=gen, dtype=torch.float32)
+    if integer_fraction > 0:
+        pick = torch.rand((cfg.N, Ho, Wo, cfg.G, K), generator=gen) < integer_fraction
+        off = torch.where(pick[..., None], torch.round(off), off)
+    out = {"x": x, "offset": off, "mask": m, "grad_y": gy}
+    np_dtype = {"f32": np.float32, "f16": np.float16}[dtype]
+    return {k: v.numpy().astype(np_dtype) for k, v in out.items()}
