@@ -1,0 +1,107 @@
+/*
+ * dcnv4.h -- C ABI of the MI355X (gfx950) DCNv4 spatial-aggregation library.
+ *
+ * The operator (paper Sec. 3.1, Eq. 1-2, with the softmax over the taps removed as
+ * "Enhancing dynamic property" prescribes; thread/channel organisation after
+ * Sec. 3.2 "Eliminating redundant workload / memory instructions"):
+ *
+ *   y[n,oh,ow,g*Cg+c] = sum_{k} m[n,oh,ow,g,k] * bilinear(x[n,:,:,g*Cg+c], hy_k, wx_k)
+ *   hy_k = oh*stride_h - pad_h + i*dil_h + offset_scale * offset[n,oh,ow,g,k,1]
+ *   wx_k = ow*stride_w - pad_w + j*dil_w + offset_scale * offset[n,oh,ow,g,k,0]
+ *   k = j*kernel_h + i   (j: window column, slow; i: window row, fast)
+ *
+ * Whole-number coordinates are pixel centres; the four neighbours are floor and
+ * floor+1; a neighbour outside the image reads zero.  m is used as given
+ * (unbounded, not normalised).
+ *
+ * Memory: every tensor pointer is a DEVICE pointer owned by the caller, dense and
+ * contiguous, 16-byte aligned, all of one element type `dtype`:
+ *   x, grad_x            [N, H,  W,  G*Cg]     channel-last
+ *   offset, grad_offset  [N, Ho, Wo, G, 9, 2]
+ *   mask, grad_mask      [N, Ho, Wo, G, 9]
+ *   y, grad_y            [N, Ho, Wo, G*Cg]
+ * with (Ho, Wo) as returned by dcnv4_output_hw().  The library keeps no state,
+ * allocates nothing, enqueues its kernels on `stream` (a hipStream_t, NULL = the
+ * default stream) and returns without synchronising.  Outputs must not alias inputs.
+ *
+ * Supported: kernel 3x3; stride, dilation >= 1; pad >= 0; Cg in {8, 16, 32, 64};
+ * dtype F32 or F16 (fp16 storage, fp32 positions, weights and accumulation, one
+ * round-to-nearest at the store) for the forward; F32 for the backward.  One
+ * image of x (H*W*G*Cg elements) must stay below 1 GiB.
+ *
+ * Errors: every call validates its arguments on the host first and returns a
+ * nonzero DCNV4_ERR_* without launching or writing anything; nothing throws or
+ * aborts.  DCNV4_ERR_LAUNCH reports a HIP launch failure.
+ */
+#ifndef DCNV4_H
+#define DCNV4_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { DCNV4_F32 = 0, DCNV4_F16 = 1 };
+
+enum {
+    DCNV4_OK = 0,
+    DCNV4_ERR_NULL = 1,        /* a required pointer is NULL */
+    DCNV4_ERR_SHAPE = 2,       /* a size is non-positive or the window does not fit */
+    DCNV4_ERR_UNSUPPORTED = 3, /* kernel size, Cg, dtype or tensor size outside the supported set */
+    DCNV4_ERR_ALIGN = 4,       /* a tensor pointer is not 16-byte aligned */
+    DCNV4_ERR_LAUNCH = 5       /* the HIP runtime refused the launch */
+};
+
+/* Output extent of the sliding window: Ho = (H + 2*pad_h - dil_h*(kernel_h-1) - 1)/stride_h + 1,
+ * likewise Wo (Sec. 3.1: the operator slides like a regular convolution).
+ * Host pointers H_out/W_out; returns DCNV4_ERR_SHAPE if the window does not fit. */
+int dcnv4_output_hw(int H, int W, int kernel_h, int kernel_w, int stride_h, int stride_w,
+                    int pad_h, int pad_w, int dil_h, int dil_w, int *H_out, int *W_out);
+
+/* Forward aggregation, Eq. 1-2 (gather the 4 neighbours of each of the 9 taps for a run of
+ * channels, interpolate, modulate by m, reduce over the taps).  Overwrites y. */
+int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y,
+                  int N, int H, int W, int G, int Cg,
+                  int kernel_h, int kernel_w, int stride_h, int stride_w,
+                  int pad_h, int pad_w, int dil_h, int dil_w,
+                  float offset_scale, int dtype, void *stream);
+
+/* Backward of Eq. 1 by the chain rule (the paper gives no backward):
+ *   grad_mask_k  = sum_c gy[c] * S_k[c]
+ *   grad_offset  = offset_scale * m_k * sum_c gy[c] * dS_k[c]/d(wx, hy)   (right-hand derivative
+ *                  at whole-number coordinates)
+ *   grad_x      += m_k * corner weight * gy[c]   at the in-image neighbours (fp32 atomics)
+ * Overwrites all three outputs; grad_x is zero-filled on `stream` first. */
+int dcnv4_backward(const void *x, const void *offset, const void *mask, const void *grad_y,
+                   void *grad_x, void *grad_offset, void *grad_mask,
+                   int N, int H, int W, int G, int Cg,
+                   int kernel_h, int kernel_w, int stride_h, int stride_w,
+                   int pad_h, int pad_w, int dil_h, int dil_w,
+                   float offset_scale, int dtype, void *stream);
+
+/* Bytes the ideal memory-access model of Sec. 3.2 ("2HWC + 27HWG", every value touched
+ * once) assigns to one forward call: x + offset + mask + y.  Host-only helper. */
+long long dcnv4_forward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
+                                          int H_out, int W_out, int dtype);
+
+/* Same model for one backward call: reads x, offset, mask, grad_y; writes grad_x,
+ * grad_offset, grad_mask (the zero-fill of grad_x is not counted). */
+long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
+                                           int H_out, int W_out, int dtype);
+
+/* Tuning knobs for benchmarking (process-wide, not thread-safe).  Keys:
+ *   "fwd_cpt"  channels per thread in the forward kernel (8 or 16; 0 = library default)
+ *   "bwd_cpt"  channels per thread in the backward kernel (4, 8 or 16; 0 = default)
+ *   "xcd_remap" 1 = hand consecutive tiles to one XCD (default), 0 = plain block order
+ * Returns DCNV4_ERR_UNSUPPORTED for an unknown key or value. */
+int dcnv4_set_option(const char *key, int value);
+
+/* Name of the forward / backward kernel the current options select for (dtype, Cg),
+ * as it appears in a profiler's kernel trace.  Static storage; NULL if unsupported. */
+const char *dcnv4_kernel_name(int backward, int dtype, int Cg);
+
+const char *dcnv4_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DCNV4_H */

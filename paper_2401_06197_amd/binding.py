@@ -1,0 +1,193 @@
+"""ctypes binding of include/dcnv4.h: same names, argument marshalling only.
+
+The tensor arguments are torch tensors on the GPU (torch is used for device memory and
+streams, nothing else); every step of the operator runs inside libdcnv4.so.  If the
+library has not been built the import of it fails loudly -- there is no fallback path.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdcnv4.so")
+
+DCNV4_F32, DCNV4_F16 = 0, 1
+DCNV4_OK = 0
+
+# every symbol include/dcnv4.h declares
+EXPORTS = (
+    "dcnv4_output_hw", "dcnv4_forward", "dcnv4_backward",
+    "dcnv4_forward_algorithmic_bytes", "dcnv4_backward_algorithmic_bytes",
+    "dcnv4_set_option", "dcnv4_kernel_name", "dcnv4_status_string",
+)
+
+_lib = None
+
+
+class Dcnv4Error(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: status {status} ({dcnv4_status_string(status)})")
+
+
+def load_library():
+    """Load libdcnv4.so (built in-tree by paper_2401_06197_amd.build); raise if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2401_06197_amd.build` "
+            "(the DCNv4 operator has no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.dcnv4_output_hw.argtypes = [ci] * 10 + [ip, ip]
+    lib.dcnv4_output_hw.restype = ci
+    geo = [ci] * 13 + [cf, ci, vp]
+    lib.dcnv4_forward.argtypes = [vp] * 4 + geo
+    lib.dcnv4_forward.restype = ci
+    lib.dcnv4_backward.argtypes = [vp] * 7 + geo
+    lib.dcnv4_backward.restype = ci
+    for f in (lib.dcnv4_forward_algorithmic_bytes, lib.dcnv4_backward_algorithmic_bytes):
+        f.argtypes = [ci] * 8
+        f.restype = ctypes.c_longlong
+    lib.dcnv4_set_option.argtypes = [ctypes.c_char_p, ci]
+    lib.dcnv4_set_option.restype = ci
+    lib.dcnv4_kernel_name.argtypes = [ci, ci, ci]
+    lib.dcnv4_kernel_name.restype = ctypes.c_char_p
+    lib.dcnv4_status_string.argtypes = [ci]
+    lib.dcnv4_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _pair(v):
+    return (int(v), int(v)) if isinstance(v, int) else (int(v[0]), int(v[1]))
+
+
+def dcnv4_status_string(status):
+    return load_library().dcnv4_status_string(int(status)).decode()
+
+
+def dcnv4_output_hw(H, W, kernel=3, stride=1, pad=1, dilation=1):
+    (kh, kw), (sh, sw), (ph, pw), (dh, dw) = map(_pair, (kernel, stride, pad, dilation))
+    ho, wo = ctypes.c_int(0), ctypes.c_int(0)
+    rc = load_library().dcnv4_output_hw(H, W, kh, kw, sh, sw, ph, pw, dh, dw, ctypes.byref(ho), ctypes.byref(wo))
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_output_hw")
+    return ho.value, wo.value
+
+
+def dcnv4_set_option(key, value):
+    rc = load_library().dcnv4_set_option(key.encode(), int(value))
+    if rc:
+        raise Dcnv4Error(rc, f"dcnv4_set_option({key!r}, {value})")
+
+
+def dcnv4_kernel_name(backward, dtype, Cg):
+    s = load_library().dcnv4_kernel_name(int(backward), int(dtype), int(Cg))
+    return s.decode() if s else None
+
+
+def dcnv4_forward_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype):
+    return int(load_library().dcnv4_forward_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype))
+
+
+def dcnv4_backward_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype):
+    return int(load_library().dcnv4_backward_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype))
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return DCNV4_F32
+    if t.dtype == torch.float16:
+        return DCNV4_F16
+    raise TypeError(f"dcnv4: unsupported tensor dtype {t.dtype}")
+
+
+def _check(name, t, ref):
+    if not t.is_cuda:
+        raise ValueError(f"dcnv4: {name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"dcnv4: {name} must be contiguous")
+    if t.dtype != ref.dtype or t.device != ref.device:
+        raise ValueError(f"dcnv4: {name} must share dtype and device with x")
+
+
+def _stream_ptr(stream, device):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _shape_args(x, offset, mask, kernel, stride, pad, dilation):
+    (kh, kw), (sh, sw), (ph, pw), (dh, dw) = map(_pair, (kernel, stride, pad, dilation))
+    if x.dim() != 4 or offset.dim() != 6 or mask.dim() != 5:
+        raise ValueError("dcnv4: expected x [N,H,W,C], offset [N,Ho,Wo,G,K,2], mask [N,Ho,Wo,G,K]")
+    N, H, W, C = x.shape
+    G = mask.shape[3]
+    if G < 1 or C % G:
+        raise ValueError("dcnv4: C must be a multiple of G")
+    Ho, Wo = dcnv4_output_hw(H, W, (kh, kw), (sh, sw), (ph, pw), (dh, dw))
+    K = kh * kw
+    if tuple(mask.shape) != (N, Ho, Wo, G, K) or tuple(offset.shape) != (N, Ho, Wo, G, K, 2):
+        raise ValueError(f"dcnv4: offset/mask shapes {tuple(offset.shape)}/{tuple(mask.shape)} do not match "
+                         f"N={N} Ho={Ho} Wo={Wo} G={G} K={K}")
+    return (N, H, W, G, C // G, kh, kw, sh, sw, ph, pw, dh, dw), (N, Ho, Wo, C)
+
+
+def dcnv4_forward(x, offset, mask, kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0, out=None, stream=None,
+                  prepare_only=False):
+    """y [N,Ho,Wo,C] = DCNv4 aggregation of x [N,H,W,C] (Eq. 1-2 of the paper, no softmax).
+
+    With prepare_only the checked argument tuple for load_library().dcnv4_forward is returned
+    instead of launching (for launch loops that must not pay the checks every time)."""
+    import torch
+    geo, yshape = _shape_args(x, offset, mask, kernel, stride, pad, dilation)
+    for name, t in (("x", x), ("offset", offset), ("mask", mask)):
+        _check(name, t, x)
+    if out is None:
+        out = torch.empty(yshape, dtype=x.dtype, device=x.device)
+    else:
+        _check("out", out, x)
+        if tuple(out.shape) != yshape:
+            raise ValueError("dcnv4: out has the wrong shape")
+    args = (x.data_ptr(), offset.data_ptr(), mask.data_ptr(), out.data_ptr(), *geo,
+            float(offset_scale), _dtype_code(x), _stream_ptr(stream, x.device))
+    if prepare_only:
+        return args
+    with torch.cuda.device(x.device):
+        rc = load_library().dcnv4_forward(*args)
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_forward")
+    return out
+
+
+def dcnv4_backward(x, offset, mask, grad_y, kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0,
+                   out=None, stream=None, prepare_only=False):
+    """(grad_x, grad_offset, grad_mask) of dcnv4_forward for upstream gradient grad_y."""
+    import torch
+    geo, yshape = _shape_args(x, offset, mask, kernel, stride, pad, dilation)
+    for name, t in (("x", x), ("offset", offset), ("mask", mask), ("grad_y", grad_y)):
+        _check(name, t, x)
+    if tuple(grad_y.shape) != yshape:
+        raise ValueError("dcnv4: grad_y has the wrong shape")
+    if out is None:
+        out = (torch.empty_like(x), torch.empty_like(offset), torch.empty_like(mask))
+    gx, go, gm = out
+    for name, t, ref in (("grad_x", gx, x), ("grad_offset", go, offset), ("grad_mask", gm, mask)):
+        _check(name, t, x)
+        if t.shape != ref.shape:
+            raise ValueError(f"dcnv4: {name} has the wrong shape")
+    args = (x.data_ptr(), offset.data_ptr(), mask.data_ptr(), grad_y.data_ptr(),
+            gx.data_ptr(), go.data_ptr(), gm.data_ptr(), *geo,
+            float(offset_scale), _dtype_code(x), _stream_ptr(stream, x.device))
+    if prepare_only:
+        return args
+    with torch.cuda.device(x.device):
+        rc = load_library().dcnv4_backward(*args)
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_backward")
+    return gx, go, gm

@@ -1,0 +1,736 @@
+// DCNv4 spatial aggregation for MI355X (gfx950): kernels and the C ABI of include/dcnv4.h.
+//
+// Operator: paper Sec. 3.1, Eq. 1-2 without the softmax.  Work organisation follows the
+// idea of Sec. 3.2 (one thread serves a run of channels of one group at one output pixel,
+// so one offset/mask read and one set of bilinear coefficients is shared, and the channel
+// run is moved with 128-bit memory instructions); everything below that idea is laid out
+// for CDNA4: wave64, raw buffer loads whose hardware range check supplies the zero for
+// rows outside the image, offset/mask tiles staged through LDS with 128-bit coalesced
+// loads, tiles handed to XCDs in contiguous bands so that neighbouring outputs share an L2.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "dcnv4.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTaps = 9;
+constexpr int kXcds = 8;
+// Word 3 of a gfx9-family raw buffer descriptor: 32-bit data format, no swizzle, no stride.
+constexpr int kRsrcWord3 = 0x00020000;
+// A byte offset no descriptor of ours reaches (images are validated below 2^31 bytes):
+// loads through it return zero, atomics through it are dropped.
+constexpr int kOutside = (int)0x80000000u;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+// n / d for 0 <= n < 2^31 as mulhi + add + shift (d >= 1), constants made on the host.
+struct FastDiv {
+    unsigned mul, shift;
+};
+
+__device__ __forceinline__ int fdiv(int n, FastDiv f)
+{
+    return (int)((__umulhi((unsigned)n, f.mul) + (unsigned)n) >> f.shift);
+}
+
+struct Geo {
+    int H, W, Ho, Wo, G;
+    int sh, sw, ph, pw, dh, dw;
+    float scale;        // offset_scale
+    float dmax;         // scaled offsets are clamped to [-dmax, dmax]; beyond that every corner is outside
+    int pgi;            // (pixel, group) pairs per image = Ho*Wo*G
+    int tiles_per_image, ntiles, tiles_per_xcd, remap;
+    FastDiv div_g, div_wo, div_tpi;
+    int x_img_bytes;    // H*W*C*sizeof(T)
+    int y_img_bytes;    // Ho*Wo*C*sizeof(T)
+    int row_bytes;      // W*C*sizeof(T)
+    int pix_bytes;      // C*sizeof(T)
+};
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, kRsrcWord3);
+}
+
+// blockIdx -> tile.  Hardware deals consecutive workgroups to the 8 XCDs in turn; with the
+// remap XCD i works through tiles [i*tiles_per_xcd, (i+1)*tiles_per_xcd) in order, so the
+// tiles in flight on one XCD are spatial neighbours and their input pixels hit that XCD's L2.
+__device__ __forceinline__ int tile_of_block(const Geo &p)
+{
+    const int b = blockIdx.x;
+    return p.remap ? (b & (kXcds - 1)) * p.tiles_per_xcd + (b >> 3) : b;
+}
+
+// Copy `bytes` of a tensor region starting at byte `start` (of `base`, 16-byte aligned) into
+// LDS, beginning at the 16-byte boundary below `start`; returns through `delta` how many
+// bytes of lead-in precede the region in LDS.  All global reads are aligned 128-bit loads;
+// the descriptor ends exactly at the region's end, so nothing past the tensor is touched.
+template <int CAP_BYTES>
+__device__ __forceinline__ int stage_region(char *lds, const char *base, long long start, int bytes)
+{
+    const long long aligned = start & ~15LL;
+    const int delta = (int)(start - aligned);
+    const int total = delta + bytes;                       // <= CAP_BYTES by construction
+    const rsrc_t r = make_rsrc(base + aligned, (unsigned)total);
+#pragma unroll
+    for (int o = 0; o < CAP_BYTES; o += kThreads * 16) {
+        const int off = o + (int)threadIdx.x * 16;
+        if (off < total) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+            *reinterpret_cast<u32x4 *>(lds + off) = v;
+        }
+    }
+    return delta;
+}
+
+template <typename T, int CPT> struct Vec;          // CPT channels of one pixel in registers
+template <int CPT> struct Vec<_Float16, CPT> {
+    static constexpr int kRegs = CPT / 8;
+    f16x8 v[kRegs];
+    __device__ __forceinline__ void load(rsrc_t r, int off)
+    {
+#pragma unroll
+        for (int i = 0; i < kRegs; ++i)
+            v[i] = __builtin_bit_cast(f16x8, __builtin_amdgcn_raw_buffer_load_b128(r, off + 16 * i, 0, 0));
+    }
+    __device__ __forceinline__ float get(int c) const { return (float)v[c / 8][c % 8]; }
+};
+template <int CPT> struct Vec<float, CPT> {
+    static constexpr int kRegs = CPT / 4;
+    f32x4 v[kRegs];
+    __device__ __forceinline__ void load(rsrc_t r, int off)
+    {
+#pragma unroll
+        for (int i = 0; i < kRegs; ++i)
+            v[i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, off + 16 * i, 0, 0));
+    }
+    __device__ __forceinline__ float get(int c) const { return v[c / 4][c % 4]; }
+};
+
+template <int CPT>
+__device__ __forceinline__ void store_run(rsrc_t r, int off, const float (&a)[CPT], _Float16 *)
+{
+#pragma unroll
+    for (int i = 0; i < CPT / 8; ++i) {
+        f16x8 h;
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            h[c] = (_Float16)a[8 * i + c];                 // round to nearest even, once
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, h), r, off + 16 * i, 0, 0);
+    }
+}
+template <int CPT>
+__device__ __forceinline__ void store_run(rsrc_t r, int off, const float (&a)[CPT], float *)
+{
+#pragma unroll
+    for (int i = 0; i < CPT / 4; ++i) {
+        f32x4 f = {a[4 * i], a[4 * i + 1], a[4 * i + 2], a[4 * i + 3]};
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, f), r, off + 16 * i, 0, 0);
+    }
+}
+
+// One tap's sampling geometry: fractional parts, the byte offsets of the 4 neighbours inside
+// the image's descriptor (kOutside where the column is outside; rows outside fall out of the
+// descriptor's range by themselves) -- Eq. 1's x_g(p0 + p_k + dp_gk).
+struct Tap {
+    float lh, lw;
+    int o00, o01, o10, o11;
+};
+
+__device__ __forceinline__ Tap tap_geometry(float dY, float dX, int base_h, int base_w, int chan_bytes,
+                                            const Geo &p)
+{
+    // The whole-pixel part of the sampling position is kept in integers and only the scaled
+    // offset goes through fp32, so the fractional parts carry no error from the magnitude of
+    // the pixel coordinate.
+    float dy = __builtin_fminf(__builtin_fmaxf(p.scale * dY, -p.dmax), p.dmax);
+    float dx = __builtin_fminf(__builtin_fmaxf(p.scale * dX, -p.dmax), p.dmax);
+    const float fy = __builtin_floorf(dy), fx = __builtin_floorf(dx);
+    Tap t;
+    t.lh = dy - fy;
+    t.lw = dx - fx;
+    const int h0 = base_h + (int)fy, w0 = base_w + (int)fx;
+    const int o = h0 * p.row_bytes + w0 * p.pix_bytes + chan_bytes;
+    const bool in0 = (unsigned)w0 < (unsigned)p.W, in1 = (unsigned)(w0 + 1) < (unsigned)p.W;
+    t.o00 = in0 ? o : kOutside;
+    t.o10 = in0 ? o + p.row_bytes : kOutside;
+    t.o01 = in1 ? o + p.pix_bytes : kOutside;
+    t.o11 = in1 ? o + p.row_bytes + p.pix_bytes : kOutside;
+    return t;
+}
+
+// Shared per-thread decode: which (pixel, group, channel run) this thread serves.
+struct Item {
+    int n, pg0, npg;          // image, first (pixel,group) of the tile, pairs in the tile
+    int pgl, sub;             // pair inside the tile, channel run inside the group
+    int pix, g, oh, ow;
+    bool active;
+};
+
+template <int TPG>
+__device__ __forceinline__ Item decode_item(const Geo &p, int tile)
+{
+    constexpr int PGB = kThreads / TPG;
+    Item it;
+    it.n = fdiv(tile, p.div_tpi);
+    it.pg0 = (tile - it.n * p.tiles_per_image) * PGB;
+    it.npg = min(PGB, p.pgi - it.pg0);
+    it.pgl = (int)threadIdx.x / TPG;
+    it.sub = (int)threadIdx.x % TPG;
+    it.active = it.pgl < it.npg;
+    const int pg = it.pg0 + min(it.pgl, it.npg - 1);
+    it.pix = fdiv(pg, p.div_g);
+    it.g = pg - it.pix * p.G;
+    it.oh = fdiv(it.pix, p.div_wo);
+    it.ow = it.pix - it.oh * p.Wo;
+    return it;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// Forward (Eq. 1-2): thread = (output pixel, group, run of CPT channels).
+// ------------------------------------------------------------------------------------------
+template <typename T, int CG, int CPT>
+__global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict__ x, const T *__restrict__ offset,
+                                                             const T *__restrict__ mask, T *__restrict__ y, Geo p)
+{
+    constexpr int TPG = CG / CPT;
+    constexpr int PGB = kThreads / TPG;
+    constexpr int OFF_CAP = PGB * 2 * kTaps * (int)sizeof(T) + 16;
+    constexpr int MSK_CAP = PGB * kTaps * (int)sizeof(T) + 16;
+    __shared__ __attribute__((aligned(16))) char s_off[OFF_CAP];
+    __shared__ __attribute__((aligned(16))) char s_msk[MSK_CAP];
+
+    const int tile = tile_of_block(p);
+    if (tile >= p.ntiles)
+        return;
+    const Item it = decode_item<TPG>(p, tile);
+
+    const long long pg_first = (long long)it.n * p.pgi + it.pg0;
+    const int d_off = stage_region<OFF_CAP>(s_off, (const char *)offset, pg_first * (2 * kTaps * (int)sizeof(T)),
+                                            it.npg * 2 * kTaps * (int)sizeof(T));
+    const int d_msk = stage_region<MSK_CAP>(s_msk, (const char *)mask, pg_first * (kTaps * (int)sizeof(T)),
+                                            it.npg * kTaps * (int)sizeof(T));
+    __syncthreads();
+    if (!it.active)
+        return;
+
+    const T *my_off = reinterpret_cast<const T *>(s_off + d_off) + it.pgl * 2 * kTaps;
+    const T *my_msk = reinterpret_cast<const T *>(s_msk + d_msk) + it.pgl * kTaps;
+    const rsrc_t rx = make_rsrc((const char *)x + (long long)it.n * p.x_img_bytes, (unsigned)p.x_img_bytes);
+    const int chan_bytes = (it.g * CG + it.sub * CPT) * (int)sizeof(T);
+    const int bh = it.oh * p.sh - p.ph, bw = it.ow * p.sw - p.pw;
+
+    float acc[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c)
+        acc[c] = 0.f;
+
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int k = j * 3 + i;
+            const Tap t = tap_geometry((float)my_off[2 * k + 1], (float)my_off[2 * k], bh + i * p.dh, bw + j * p.dw,
+                                       chan_bytes, p);
+            Vec<T, CPT> v00, v01, v10, v11;
+            v00.load(rx, t.o00);
+            v01.load(rx, t.o01);
+            v10.load(rx, t.o10);
+            v11.load(rx, t.o11);
+            const float m = (float)my_msk[k];
+            const float mh0 = m * (1.f - t.lh), mh1 = m * t.lh;
+            const float w00 = mh0 * (1.f - t.lw), w01 = mh0 * t.lw, w10 = mh1 * (1.f - t.lw), w11 = mh1 * t.lw;
+#pragma unroll
+            for (int c = 0; c < CPT; ++c) {
+                float a = acc[c];
+                a = __builtin_fmaf(v00.get(c), w00, a);
+                a = __builtin_fmaf(v01.get(c), w01, a);
+                a = __builtin_fmaf(v10.get(c), w10, a);
+                a = __builtin_fmaf(v11.get(c), w11, a);
+                acc[c] = a;
+            }
+        }
+    }
+
+    const rsrc_t ry = make_rsrc((char *)y + (long long)it.n * p.y_img_bytes, (unsigned)p.y_img_bytes);
+    store_run<CPT>(ry, it.pix * p.pix_bytes + chan_bytes, acc, (T *)nullptr);
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward (chain rule on Eq. 1), fp32.  Same thread organisation as the forward.  The
+// per-channel products are reduced inside the thread; when a group is split over TPG lanes
+// the partial sums are combined with DPP lane exchanges inside one 16-lane row.
+// grad_offset / grad_mask leave through the same LDS tile the inputs came in by.
+// ------------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false);
+    return v + __builtin_bit_cast(float, o);
+}
+
+template <int TPG>
+__device__ __forceinline__ float group_sum(float v)
+{
+    if (TPG >= 2) v = dpp_add<0xB1>(v);      // quad_perm [1,0,3,2]
+    if (TPG >= 4) v = dpp_add<0x4E>(v);      // quad_perm [2,3,0,1]
+    if (TPG >= 8) v = dpp_add<0x141>(v);     // row_half_mirror
+    if (TPG >= 16) v = dpp_add<0x140>(v);    // row_mirror
+    return v;
+}
+
+template <int CG, int CPT>
+__global__ __launch_bounds__(kThreads) void dcnv4_bwd_kernel(const float *__restrict__ x,
+                                                             const float *__restrict__ offset,
+                                                             const float *__restrict__ mask,
+                                                             const float *__restrict__ grad_y,
+                                                             float *__restrict__ grad_x,
+                                                             float *__restrict__ grad_offset,
+                                                             float *__restrict__ grad_mask, Geo p)
+{
+    typedef float T;
+    constexpr int TPG = CG / CPT;
+    constexpr int PGB = kThreads / TPG;
+    constexpr int OFF_CAP = PGB * 2 * kTaps * (int)sizeof(T) + 16;
+    constexpr int MSK_CAP = PGB * kTaps * (int)sizeof(T) + 16;
+    __shared__ __attribute__((aligned(16))) char s_off[OFF_CAP];
+    __shared__ __attribute__((aligned(16))) char s_msk[MSK_CAP];
+
+    const int tile = tile_of_block(p);
+    if (tile >= p.ntiles)
+        return;
+    const Item it = decode_item<TPG>(p, tile);
+
+    const long long pg_first = (long long)it.n * p.pgi + it.pg0;
+    const int d_off = stage_region<OFF_CAP>(s_off, (const char *)offset, pg_first * (2 * kTaps * (int)sizeof(T)),
+                                            it.npg * 2 * kTaps * (int)sizeof(T));
+    const int d_msk = stage_region<MSK_CAP>(s_msk, (const char *)mask, pg_first * (kTaps * (int)sizeof(T)),
+                                            it.npg * kTaps * (int)sizeof(T));
+    __syncthreads();
+
+    T *tile_off = reinterpret_cast<T *>(s_off + d_off);
+    T *tile_msk = reinterpret_cast<T *>(s_msk + d_msk);
+    if (it.active) {
+        T *my_off = tile_off + it.pgl * 2 * kTaps;
+        T *my_msk = tile_msk + it.pgl * kTaps;
+        const rsrc_t rx = make_rsrc((const char *)x + (long long)it.n * p.x_img_bytes, (unsigned)p.x_img_bytes);
+        const rsrc_t rgx = make_rsrc((char *)grad_x + (long long)it.n * p.x_img_bytes, (unsigned)p.x_img_bytes);
+        const rsrc_t rgy =
+            make_rsrc((const char *)grad_y + (long long)it.n * p.y_img_bytes, (unsigned)p.y_img_bytes);
+        const int chan_bytes = (it.g * CG + it.sub * CPT) * (int)sizeof(T);
+        const int bh = it.oh * p.sh - p.ph, bw = it.ow * p.sw - p.pw;
+
+        Vec<T, CPT> gy;
+        gy.load(rgy, it.pix * p.pix_bytes + chan_bytes);
+
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int k = j * 3 + i;
+                const Tap t = tap_geometry(my_off[2 * k + 1], my_off[2 * k], bh + i * p.dh, bw + j * p.dw,
+                                           chan_bytes, p);
+                Vec<T, CPT> v00, v01, v10, v11;
+                v00.load(rx, t.o00);
+                v01.load(rx, t.o01);
+                v10.load(rx, t.o10);
+                v11.load(rx, t.o11);
+                const float m = my_msk[k];
+                const float hh = 1.f - t.lh, hw = 1.f - t.lw;
+                // grad_x: m * corner weight * gy, dropped by the descriptor where the corner is outside
+                const float w00 = m * hh * hw, w01 = m * hh * t.lw, w10 = m * t.lh * hw, w11 = m * t.lh * t.lw;
+                float d00 = 0.f, d01 = 0.f, d10 = 0.f, d11 = 0.f;
+#pragma unroll
+                for (int c = 0; c < CPT; ++c) {
+                    const float g = gy.get(c);
+                    d00 = __builtin_fmaf(g, v00.get(c), d00);
+                    d01 = __builtin_fmaf(g, v01.get(c), d01);
+                    d10 = __builtin_fmaf(g, v10.get(c), d10);
+                    d11 = __builtin_fmaf(g, v11.get(c), d11);
+                    __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(w00 * g, rgx, t.o00 + 4 * c, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(w01 * g, rgx, t.o01 + 4 * c, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(w10 * g, rgx, t.o10 + 4 * c, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(w11 * g, rgx, t.o11 + 4 * c, 0, 0);
+                }
+                d00 = group_sum<TPG>(d00);
+                d01 = group_sum<TPG>(d01);
+                d10 = group_sum<TPG>(d10);
+                d11 = group_sum<TPG>(d11);
+                // grad_mask = sum_c gy*S;  grad_offset = scale * m * sum_c gy * dS/d(wx, hy)
+                const float gm = hh * (hw * d00 + t.lw * d01) + t.lh * (hw * d10 + t.lw * d11);
+                const float gdy = p.scale * m * (hw * (d10 - d00) + t.lw * (d11 - d01));
+                const float gdx = p.scale * m * (hh * (d01 - d00) + t.lh * (d11 - d10));
+                if (it.sub == 0) {                       // after every lane of the pair has read tap k
+                    my_off[2 * k] = gdx;
+                    my_off[2 * k + 1] = gdy;
+                    my_msk[k] = gm;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    float *go = grad_offset + pg_first * (2 * kTaps);
+    float *gm = grad_mask + pg_first * kTaps;
+    for (int e = threadIdx.x; e < it.npg * 2 * kTaps; e += kThreads)
+        go[e] = tile_off[e];
+    for (int e = threadIdx.x; e < it.npg * kTaps; e += kThreads)
+        gm[e] = tile_msk[e];
+}
+
+__global__ __launch_bounds__(kThreads) void dcnv4_zero_kernel(u32x4 *__restrict__ dst, long long n16)
+{
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (long long)gridDim.x * kThreads)
+        dst[i] = z;
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side: validation, launch geometry, dispatch.
+// ------------------------------------------------------------------------------------------
+namespace {
+
+struct Options {
+    int fwd_cpt = 0, bwd_cpt = 0, xcd_remap = 1;
+} g_opt;
+
+FastDiv make_div(unsigned d)
+{
+    unsigned s = 0;
+    while ((1ull << s) < d)
+        ++s;
+    FastDiv f;
+    f.shift = s;
+    f.mul = (unsigned)(((1ull << 32) * ((1ull << s) - d)) / d + 1);
+    return f;
+}
+
+int esize(int dtype) { return dtype == DCNV4_F16 ? 2 : 4; }
+
+struct Problem {
+    int N, H, W, G, Cg, Ho, Wo;
+    int sh, sw, ph, pw, dh, dw;
+    float scale;
+    int dtype;
+};
+
+int validate(const Problem &q, int kh, int kw, const void *const *ptrs, int nptrs)
+{
+    for (int i = 0; i < nptrs; ++i)
+        if (!ptrs[i])
+            return DCNV4_ERR_NULL;
+    if (q.N < 1 || q.H < 1 || q.W < 1 || q.G < 1 || q.Cg < 1 || kh < 1 || kw < 1 || q.sh < 1 || q.sw < 1 ||
+        q.ph < 0 || q.pw < 0 || q.dh < 1 || q.dw < 1)
+        return DCNV4_ERR_SHAPE;
+    if (q.Ho < 1 || q.Wo < 1)
+        return DCNV4_ERR_SHAPE;
+    if (kh != 3 || kw != 3)
+        return DCNV4_ERR_UNSUPPORTED;
+    if (q.dtype != DCNV4_F32 && q.dtype != DCNV4_F16)
+        return DCNV4_ERR_UNSUPPORTED;
+    if (q.Cg != 8 && q.Cg != 16 && q.Cg != 32 && q.Cg != 64)
+        return DCNV4_ERR_UNSUPPORTED;
+    if (!(q.scale == q.scale) || q.scale > 3.0e38f || q.scale < -3.0e38f)
+        return DCNV4_ERR_UNSUPPORTED;
+    for (int i = 0; i < nptrs; ++i)
+        if (reinterpret_cast<uintptr_t>(ptrs[i]) & 15u)
+            return DCNV4_ERR_ALIGN;
+    return DCNV4_OK;
+}
+
+// Fills the kernel's geometry block; returns DCNV4_ERR_UNSUPPORTED when 32-bit byte offsets
+// inside one image could overflow.
+int make_geo(const Problem &q, int tpg, Geo *out)
+{
+    Geo p;
+    memset(&p, 0, sizeof(p));
+    const long long es = esize(q.dtype), C = (long long)q.G * q.Cg;
+    p.H = q.H; p.W = q.W; p.Ho = q.Ho; p.Wo = q.Wo; p.G = q.G;
+    p.sh = q.sh; p.sw = q.sw; p.ph = q.ph; p.pw = q.pw; p.dh = q.dh; p.dw = q.dw;
+    p.scale = q.scale;
+    // window origin of any tap lies in [-pad, (out-1)*stride - pad + 2*dil]
+    const long long bh = (long long)(q.Ho - 1) * q.sh + 2LL * q.dh + q.ph;
+    const long long bw = (long long)(q.Wo - 1) * q.sw + 2LL * q.dw + q.pw;
+    const long long reach = (q.H > q.W ? q.H : q.W) + (bh > bw ? bh : bw) + 4;
+    if (reach >= (1 << 22))
+        return DCNV4_ERR_UNSUPPORTED;
+    p.dmax = (float)reach;
+    // |row| <= 2*reach+1, |col| <= 2*reach+1 after clamping: the byte offset must fit in int32
+    const long long worst = (2 * reach + 2) * ((long long)q.W + 1) * C * es + (2 * reach + 2) * C * es;
+    const long long ximg = (long long)q.H * q.W * C * es, yimg = (long long)q.Ho * q.Wo * C * es;
+    if (worst >= (1LL << 31) || ximg >= (1LL << 31) || yimg >= (1LL << 31))
+        return DCNV4_ERR_UNSUPPORTED;
+    const long long pgi = (long long)q.Ho * q.Wo * q.G;
+    const int pgb = kThreads / tpg;
+    const long long tpi = (pgi + pgb - 1) / pgb;
+    const long long ntiles = tpi * q.N;
+    if (pgi >= (1LL << 31) || ntiles >= (1LL << 30))
+        return DCNV4_ERR_UNSUPPORTED;
+    p.pgi = (int)pgi;
+    p.tiles_per_image = (int)tpi;
+    p.ntiles = (int)ntiles;
+    p.tiles_per_xcd = (int)((ntiles + kXcds - 1) / kXcds);
+    p.remap = g_opt.xcd_remap;
+    p.div_g = make_div((unsigned)q.G);
+    p.div_wo = make_div((unsigned)q.Wo);
+    p.div_tpi = make_div((unsigned)tpi);
+    p.x_img_bytes = (int)ximg;
+    p.y_img_bytes = (int)yimg;
+    p.row_bytes = (int)(q.W * C * es);
+    p.pix_bytes = (int)(C * es);
+    *out = p;
+    return DCNV4_OK;
+}
+
+unsigned grid_of(const Geo &p) { return (unsigned)(p.remap ? p.tiles_per_xcd * kXcds : p.ntiles); }
+
+int default_fwd_cpt(int dtype, int Cg)
+{
+    if (Cg == 8) return 8;
+    return dtype == DCNV4_F16 ? 16 : 8;
+}
+int default_bwd_cpt(int Cg) { return Cg == 8 ? 8 : 8; }
+
+int pick_fwd_cpt(int dtype, int Cg)
+{
+    int c = g_opt.fwd_cpt ? g_opt.fwd_cpt : default_fwd_cpt(dtype, Cg);
+    if (c > Cg) c = Cg;
+    if (Cg / c > 8) c = Cg / 8;        // at most 8 lanes per group
+    return c;
+}
+int pick_bwd_cpt(int Cg)
+{
+    int c = g_opt.bwd_cpt ? g_opt.bwd_cpt : default_bwd_cpt(Cg);
+    if (c > Cg) c = Cg;
+    if (Cg / c > 16) c = Cg / 16;      // the lane reduction stays inside one 16-lane row
+    return c;
+}
+
+template <typename T, int CG, int CPT>
+int launch_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    Geo p;
+    int rc = make_geo(q, CG / CPT, &p);
+    if (rc)
+        return rc;
+    hipLaunchKernelGGL((dcnv4_fwd_kernel<T, CG, CPT>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const T *)x,
+                       (const T *)off, (const T *)msk, (T *)y, p);
+    return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
+template <typename T, int CG>
+int dispatch_fwd_cpt(int cpt, const void *x, const void *off, const void *msk, void *y, const Problem &q,
+                     hipStream_t s)
+{
+    if constexpr (CG >= 16) {
+        if (cpt == 16) return launch_fwd<T, CG, 16>(x, off, msk, y, q, s);
+    }
+    if constexpr (CG <= 64) {
+        if (cpt == 8) return launch_fwd<T, CG, 8>(x, off, msk, y, q, s);
+    }
+    return DCNV4_ERR_UNSUPPORTED;
+}
+
+template <typename T>
+int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    const int cpt = pick_fwd_cpt(q.dtype, q.Cg);
+    switch (q.Cg) {
+    case 8: return dispatch_fwd_cpt<T, 8>(cpt, x, off, msk, y, q, s);
+    case 16: return dispatch_fwd_cpt<T, 16>(cpt, x, off, msk, y, q, s);
+    case 32: return dispatch_fwd_cpt<T, 32>(cpt, x, off, msk, y, q, s);
+    case 64: return dispatch_fwd_cpt<T, 64>(cpt, x, off, msk, y, q, s);
+    }
+    return DCNV4_ERR_UNSUPPORTED;
+}
+
+template <int CG, int CPT>
+int launch_bwd(const void *x, const void *off, const void *msk, const void *gy, void *gx, void *go, void *gm,
+               const Problem &q, hipStream_t s)
+{
+    Geo p;
+    int rc = make_geo(q, CG / CPT, &p);
+    if (rc)
+        return rc;
+    const long long n16 = (long long)q.N * p.x_img_bytes / 16;    // C*4 bytes per pixel is a multiple of 16
+    long long zb = (n16 + kThreads - 1) / kThreads;
+    if (zb > 8192) zb = 8192;
+    hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)gx, n16);
+    hipLaunchKernelGGL((dcnv4_bwd_kernel<CG, CPT>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const float *)x,
+                       (const float *)off, (const float *)msk, (const float *)gy, (float *)gx, (float *)go,
+                       (float *)gm, p);
+    return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
+template <int CG>
+int dispatch_bwd_cpt(int cpt, const void *x, const void *off, const void *msk, const void *gy, void *gx, void *go,
+                     void *gm, const Problem &q, hipStream_t s)
+{
+    if constexpr (CG >= 16) {
+        if (cpt == 16) return launch_bwd<CG, 16>(x, off, msk, gy, gx, go, gm, q, s);
+    }
+    if (cpt == 8) return launch_bwd<CG, 8>(x, off, msk, gy, gx, go, gm, q, s);
+    if constexpr (CG <= 64) {
+        if (cpt == 4) return launch_bwd<CG, 4>(x, off, msk, gy, gx, go, gm, q, s);
+    }
+    return DCNV4_ERR_UNSUPPORTED;
+}
+
+int fill_problem(Problem *q, int N, int H, int W, int G, int Cg, int kh, int kw, int sh, int sw, int ph, int pw,
+                 int dh, int dw, float scale, int dtype)
+{
+    q->N = N; q->H = H; q->W = W; q->G = G; q->Cg = Cg;
+    q->sh = sh; q->sw = sw; q->ph = ph; q->pw = pw; q->dh = dh; q->dw = dw;
+    q->scale = scale; q->dtype = dtype;
+    q->Ho = q->Wo = 0;
+    if (H < 1 || W < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1)
+        return DCNV4_ERR_SHAPE;
+    return dcnv4_output_hw(H, W, kh, kw, sh, sw, ph, pw, dh, dw, &q->Ho, &q->Wo);
+}
+
+char g_name[96];
+
+}  // namespace
+
+extern "C" {
+
+int dcnv4_output_hw(int H, int W, int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w,
+                    int dil_h, int dil_w, int *H_out, int *W_out)
+{
+    if (!H_out || !W_out)
+        return DCNV4_ERR_NULL;
+    if (H < 1 || W < 1 || kernel_h < 1 || kernel_w < 1 || stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 ||
+        dil_h < 1 || dil_w < 1)
+        return DCNV4_ERR_SHAPE;
+    const long long eh = (long long)H + 2LL * pad_h - (long long)dil_h * (kernel_h - 1) - 1;
+    const long long ew = (long long)W + 2LL * pad_w - (long long)dil_w * (kernel_w - 1) - 1;
+    if (eh < 0 || ew < 0)
+        return DCNV4_ERR_SHAPE;
+    *H_out = (int)(eh / stride_h + 1);
+    *W_out = (int)(ew / stride_w + 1);
+    return DCNV4_OK;
+}
+
+int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y, int N, int H, int W, int G, int Cg,
+                  int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                  float offset_scale, int dtype, void *stream)
+{
+    const void *ptrs[4] = {x, offset, mask, y};
+    for (const void *ptr : ptrs)
+        if (!ptr)
+            return DCNV4_ERR_NULL;
+    Problem q;
+    int rc = fill_problem(&q, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                          offset_scale, dtype);
+    if (rc)
+        return rc;
+    rc = validate(q, kernel_h, kernel_w, ptrs, 4);
+    if (rc)
+        return rc;
+    hipStream_t s = (hipStream_t)stream;
+    return dtype == DCNV4_F16 ? dispatch_fwd<_Float16>(x, offset, mask, y, q, s)
+                              : dispatch_fwd<float>(x, offset, mask, y, q, s);
+}
+
+int dcnv4_backward(const void *x, const void *offset, const void *mask, const void *grad_y, void *grad_x,
+                   void *grad_offset, void *grad_mask, int N, int H, int W, int G, int Cg, int kernel_h,
+                   int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                   float offset_scale, int dtype, void *stream)
+{
+    const void *ptrs[7] = {x, offset, mask, grad_y, grad_x, grad_offset, grad_mask};
+    for (const void *ptr : ptrs)
+        if (!ptr)
+            return DCNV4_ERR_NULL;
+    Problem q;
+    int rc = fill_problem(&q, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                          offset_scale, dtype);
+    if (rc)
+        return rc;
+    rc = validate(q, kernel_h, kernel_w, ptrs, 7);
+    if (rc)
+        return rc;
+    if (dtype != DCNV4_F32)
+        return DCNV4_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    const int cpt = pick_bwd_cpt(Cg);
+    switch (Cg) {
+    case 8: return dispatch_bwd_cpt<8>(cpt, x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+    case 16: return dispatch_bwd_cpt<16>(cpt, x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+    case 32: return dispatch_bwd_cpt<32>(cpt, x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+    case 64: return dispatch_bwd_cpt<64>(cpt, x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+    }
+    return DCNV4_ERR_UNSUPPORTED;
+}
+
+long long dcnv4_forward_algorithmic_bytes(int N, int H, int W, int G, int Cg, int H_out, int W_out, int dtype)
+{
+    const long long es = esize(dtype), C = (long long)G * Cg;
+    const long long P = (long long)N * H_out * W_out;
+    return es * ((long long)N * H * W * C + P * C + P * G * 27);
+}
+
+long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg, int H_out, int W_out, int dtype)
+{
+    const long long es = esize(dtype), C = (long long)G * Cg;
+    const long long P = (long long)N * H_out * W_out;
+    return es * (2 * (long long)N * H * W * C + P * C + 2 * P * G * 27);
+}
+
+int dcnv4_set_option(const char *key, int value)
+{
+    if (!key)
+        return DCNV4_ERR_NULL;
+    if (!strcmp(key, "fwd_cpt") && (value == 0 || value == 8 || value == 16)) {
+        g_opt.fwd_cpt = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "bwd_cpt") && (value == 0 || value == 4 || value == 8 || value == 16)) {
+        g_opt.bwd_cpt = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "xcd_remap") && (value == 0 || value == 1)) {
+        g_opt.xcd_remap = value;
+        return DCNV4_OK;
+    }
+    return DCNV4_ERR_UNSUPPORTED;
+}
+
+const char *dcnv4_kernel_name(int backward, int dtype, int Cg)
+{
+    if (Cg != 8 && Cg != 16 && Cg != 32 && Cg != 64)
+        return nullptr;
+    if (backward) {
+        if (dtype != DCNV4_F32)
+            return nullptr;
+        snprintf(g_name, sizeof(g_name), "dcnv4_bwd_kernel<%d, %d>", Cg, pick_bwd_cpt(Cg));
+    } else {
+        if (dtype != DCNV4_F32 && dtype != DCNV4_F16)
+            return nullptr;
+        snprintf(g_name, sizeof(g_name), "dcnv4_fwd_kernel<%s, %d, %d>", dtype == DCNV4_F16 ? "_Float16" : "float", Cg,
+                 pick_fwd_cpt(dtype, Cg));
+    }
+    return g_name;
+}
+
+const char *dcnv4_status_string(int status)
+{
+    switch (status) {
+    case DCNV4_OK: return "ok";
+    case DCNV4_ERR_NULL: return "null pointer";
+    case DCNV4_ERR_SHAPE: return "bad shape: a size is non-positive or the window does not fit";
+    case DCNV4_ERR_UNSUPPORTED: return "unsupported kernel size, group width, dtype, option or tensor size";
+    case DCNV4_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    case DCNV4_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2401_06197_amd import binding as dcn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = 4096  # a nonzero, 16-byte aligned fake address; validation never dereferences it
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dcnv4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dcnv4_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = dcn.load_library()
+    names = declared_functions()
+    assert "dcnv4_forward" in names and "dcnv4_backward" in names and len(names) >= 8
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(dcn.EXPORTS) == names
+
+
+def fwd(lib, x=A, off=A, m=A, y=A, N=1, H=14, W=14, G=4, Cg=16, k=(3, 3), s=(1, 1), p=(1, 1), d=(1, 1),
+        scale=1.0, dtype=0):
+    return lib.dcnv4_forward(x, off, m, y, N, H, W, G, Cg, k[0], k[1], s[0], s[1], p[0], p[1], d[0], d[1],
+                             scale, dtype, None)
+
+
+def bwd(lib, ptrs=(A,) * 7, N=1, H=14, W=14, G=4, Cg=16, k=(3, 3), dtype=0):
+    return lib.dcnv4_backward(*ptrs, N, H, W, G, Cg, k[0], k[1], 1, 1, 1, 1, 1, 1, 1.0, dtype, None)
+
+
+def test_forward_argument_validation_happens_on_the_host():
+    lib = dcn.load_library()
+    assert fwd(lib, x=None) == 1 and fwd(lib, off=None) == 1 and fwd(lib, m=None) == 1 and fwd(lib, y=None) == 1
+    assert fwd(lib, N=0) == 2 and fwd(lib, H=0) == 2 and fwd(lib, G=0) == 2 and fwd(lib, s=(0, 1)) == 2
+    assert fwd(lib, p=(-1, 0)) == 2 and fwd(lib, d=(1, 0)) == 2
+    assert fwd(lib, H=2, W=2, p=(0, 0)) == 2                     # 3x3 window does not fit
+    assert fwd(lib, k=(5, 5), p=(2, 2)) == 3 and fwd(lib, k=(1, 1), p=(0, 0)) == 3
+    assert fwd(lib, Cg=12) == 3 and fwd(lib, Cg=128) == 3 and fwd(lib, dtype=2) == 3
+    assert fwd(lib, scale=float("nan")) == 3 and fwd(lib, scale=float("inf")) == 3
+    assert fwd(lib, x=A + 8) == 4 and fwd(lib, y=A + 2) == 4 and fwd(lib, m=A + 4) == 4
+    # one image too large for 32-bit byte offsets
+    assert fwd(lib, H=8192, W=8192, G=16, Cg=16) == 3
+    assert fwd(lib, H=1 << 22, W=1, G=1, Cg=16, p=(1, 1)) == 3
+
+
+def test_backward_argument_validation_happens_on_the_host():
+    lib = dcn.load_library()
+    for i in range(7):
+        ptrs = [A] * 7
+        ptrs[i] = None
+        assert bwd(lib, tuple(ptrs)) == 1
+    ptrs = [A] * 7
+    ptrs[4] = A + 4
+    assert bwd(lib, tuple(ptrs)) == 4
+    assert bwd(lib, k=(3, 5)) == 3
+    assert bwd(lib, dtype=1) == 3                                 # fp16 backward is not offered
+    assert bwd(lib, N=-1) == 2
+
+
+def test_options_and_kernel_names():
+    assert dcn.dcnv4_kernel_name(0, dcn.DCNV4_F16, 16).startswith("dcnv4_fwd_kernel<_Float16, 16,")
+    assert dcn.dcnv4_kernel_name(1, dcn.DCNV4_F32, 16).startswith("dcnv4_bwd_kernel<16,")
+    assert dcn.dcnv4_kernel_name(1, dcn.DCNV4_F16, 16) is None and dcn.dcnv4_kernel_name(0, 0, 12) is None
+    with pytest.raises(dcn.Dcnv4Error):
+        dcn.dcnv4_set_option("fwd_cpt", 5)
+    with pytest.raises(dcn.Dcnv4Error):
+        dcn.dcnv4_set_option("nonsense", 1)
+    dcn.dcnv4_set_option("fwd_cpt", 8)
+    assert dcn.dcnv4_kernel_name(0, dcn.DCNV4_F16, 16) == "dcnv4_fwd_kernel<_Float16, 16, 8>"
+    dcn.dcnv4_set_option("fwd_cpt", 0)
+    assert "aligned" in dcn.dcnv4_status_string(4) and dcn.dcnv4_status_string(0) == "ok"
+
+
+@pytest.mark.parametrize("H,W,k,s,p,d", [(56, 56, 3, 1, 1, 1), (15, 14, 3, 2, 1, 1), (16, 13, 3, 1, 2, 2),
+                                          (17, 19, 3, 3, 2, 2), (9, 9, 3, 1, 0, 1), (200, 336, 3, 1, 1, 1)])
+def test_output_hw_matches_sliding_window_rule(H, W, k, s, p, d):
+    assert dcn.dcnv4_output_hw(H, W, k, s, p, d) == oracle.output_hw(H, W, k, s, p, d)
+    ho, wo = dcn.dcnv4_output_hw(H, W, k, s, p, d)
+    # last window starts inside the padded image and the next one would not fit
+    assert (ho - 1) * s + d * (k - 1) + 1 <= H + 2 * p < ho * s + d * (k - 1) + 1
+
+
+def test_algorithmic_bytes_follow_the_ideal_memory_access_model():
+    # Sec. 3.2: 2*H*W*C + 27*H*W*G values, each touched once
+    assert dcn.dcnv4_forward_algorithmic_bytes(64, 56, 56, 8, 16, 56, 56, dcn.DCNV4_F16) == 189_464_576
+    assert dcn.dcnv4_forward_algorithmic_bytes(64, 56, 56, 8, 16, 56, 56, dcn.DCNV4_F32) == 378_929_152
+    assert dcn.dcnv4_forward_algorithmic_bytes(2, 200, 336, 16, 16, 200, 336, dcn.DCNV4_F16) == 253_747_200
+    assert dcn.dcnv4_backward_algorithmic_bytes(64, 56, 56, 8, 16, 56, 56, dcn.DCNV4_F32) == 655_097_856
+    N, H, W, G, Cg = 3, 10, 12, 2, 32
+    assert dcn.dcnv4_forward_algorithmic_bytes(N, H, W, G, Cg, H, W, 0) == 4 * N * H * W * (2 * G * Cg + 27 * G)
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    monkeypatch.setattr(dcn, "_lib", None)
+    monkeypatch.setattr(dcn, "LIB_PATH", "/nonexistent/libdcnv4.so")
+    with pytest.raises(ImportError):
+        dcn.load_library()

@@ -1,0 +1,226 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on the
+same seeded inputs.  Tolerances: |gpu - ref| <= atol + rtol*|ref| with atol = rtol = 1e-5
+for fp32 and 2e-2 for fp16 storage with fp32 accumulation; `ref` is the double-precision
+oracle evaluated on the already-rounded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2401_06197_amd import binding as dcn
+from paper_2401_06197_amd.synth import CONFIGS, Config, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "f16": 2e-2}
+TORCH_DT = {"f32": torch.float32, "f16": torch.float16}
+
+
+def close(name, got, ref, tol):
+    got = got.astype(np.float64)
+    err = np.abs(got - ref)
+    lim = tol + tol * np.abs(ref)
+    bad = err > lim
+    if bad.any():
+        idx = np.unravel_index(np.argmax(err - lim), err.shape)
+        raise AssertionError(f"{name}: {int(bad.sum())} of {bad.size} outside tol {tol}; worst at {idx}: "
+                             f"got {got[idx]!r} ref {ref[idx]!r}")
+    assert np.isfinite(got).all(), f"{name}: non-finite values"
+    return float(err.max())
+
+
+def to_gpu(t, dtype):
+    return {k: torch.from_numpy(v).to("cuda", TORCH_DT[dtype]) for k, v in t.items()}
+
+
+def geo_kw(cfg):
+    return dict(kernel=cfg.kernel, stride=cfg.stride, pad=cfg.pad, dilation=cfg.dilation, offset_scale=cfg.offset_scale)
+
+
+def check_forward(cfg, dtype, seed=0, inputs=None):
+    t = inputs if inputs is not None else make_inputs(cfg, dtype, seed=seed)
+    d = to_gpu(t, dtype)
+    y = dcn.dcnv4_forward(d["x"], d["offset"], d["mask"], **geo_kw(cfg))
+    torch.cuda.synchronize()
+    ref = oracle.forward(t["x"], t["offset"], t["mask"], **geo_kw(cfg))
+    assert tuple(y.shape) == ref.shape
+    return close(f"{cfg.name}/{dtype}/y", y.cpu().numpy(), ref, TOL[dtype])
+
+
+def check_backward(cfg, seed=0, inputs=None):
+    t = inputs if inputs is not None else make_inputs(cfg, "f32", seed=seed)
+    d = to_gpu(t, "f32")
+    # poison the outputs: the call must overwrite all three
+    out = (torch.full_like(d["x"], 7.0), torch.full_like(d["offset"], 7.0), torch.full_like(d["mask"], 7.0))
+    gx, go, gm = dcn.dcnv4_backward(d["x"], d["offset"], d["mask"], d["grad_y"], out=out, **geo_kw(cfg))
+    torch.cuda.synchronize()
+    rgx, rgo, rgm = oracle.backward(t["x"], t["offset"], t["mask"], t["grad_y"], **geo_kw(cfg))
+    close(f"{cfg.name}/grad_mask", gm.cpu().numpy(), rgm, TOL["f32"])
+    close(f"{cfg.name}/grad_offset", go.cpu().numpy(), rgo, TOL["f32"])
+    close(f"{cfg.name}/grad_x", gx.cpu().numpy(), rgx, TOL["f32"])
+
+
+# ------------------------------------------------------------------ the five benchmark configs
+def test_c1_tiny_forward_backward_fp32():
+    check_forward(CONFIGS["c1"], "f32")
+    check_backward(CONFIGS["c1"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_c2_stage1_forward_full_size(dtype):
+    check_forward(CONFIGS["c2"], dtype)
+
+
+@pytest.mark.parametrize("name", ["c3_28", "c3_14", "c3_7"])
+def test_c3_stage_sweep_forward_fp16(name):
+    check_forward(CONFIGS[name], "f16")
+
+
+def test_c4_high_resolution_forward_fp16():
+    check_forward(CONFIGS["c4"], "f16")
+
+
+def test_c5_training_step_full_size_fp32():
+    check_forward(CONFIGS["c5"], "f32")
+    check_backward(CONFIGS["c5"])
+
+
+# ------------------------------------------------------------------ geometry / tiling coverage
+SMALL = [
+    # several tiles and a ragged tail per image (Ho*Wo*G not a multiple of the tile), N > 1
+    Config("rag1", N=3, H=13, W=11, C=48, G=3),
+    Config("rag2", N=2, H=9, W=17, C=80, G=5, sigma=3.0),
+    Config("cg8", N=2, H=10, W=12, C=24, G=3),
+    Config("cg32", N=2, H=12, W=9, C=96, G=3),
+    Config("cg64", N=1, H=8, W=8, C=128, G=2),
+    Config("stride2", N=2, H=15, W=14, C=32, G=2, stride=2),
+    Config("dil2", N=1, H=16, W=13, C=32, G=2, pad=2, dilation=2),
+    Config("pad0", N=1, H=9, W=9, C=16, G=1, pad=0),
+    Config("stride3_pad2_dil2", N=2, H=17, W=19, C=64, G=4, stride=3, pad=2, dilation=2, offset_scale=0.5),
+    Config("scale2", N=1, H=12, W=12, C=32, G=2, offset_scale=2.0),
+    Config("one_pixel", N=2, H=1, W=1, C=16, G=1),
+    Config("one_row", N=1, H=1, W=37, C=32, G=2),
+    Config("one_col", N=1, H=41, W=1, C=32, G=2),
+    Config("many_groups", N=1, H=6, W=5, C=1024, G=64),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_small_geometries_forward(cfg, dtype):
+    check_forward(cfg, dtype, seed=3)
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+def test_small_geometries_backward(cfg):
+    check_backward(cfg, seed=4)
+
+
+@pytest.mark.parametrize("opt,val", [("fwd_cpt", 8), ("fwd_cpt", 16), ("xcd_remap", 0)])
+def test_forward_tuning_variants_agree_with_oracle(opt, val):
+    try:
+        dcn.dcnv4_set_option(opt, val)
+        for dtype in ("f32", "f16"):
+            check_forward(Config("v", N=3, H=20, W=23, C=64, G=4), dtype, seed=5)
+            check_forward(Config("v32", N=2, H=11, W=10, C=64, G=2), dtype, seed=5)
+    finally:
+        dcn.dcnv4_set_option(opt, 0 if opt != "xcd_remap" else 1)
+
+
+@pytest.mark.parametrize("opt,val", [("bwd_cpt", 4), ("bwd_cpt", 8), ("bwd_cpt", 16), ("xcd_remap", 0)])
+def test_backward_tuning_variants_agree_with_oracle(opt, val):
+    try:
+        dcn.dcnv4_set_option(opt, val)
+        check_backward(Config("v", N=3, H=20, W=23, C=64, G=4), seed=6)
+        check_backward(Config("v32", N=2, H=11, W=10, C=64, G=2), seed=6)
+        check_backward(Config("v64", N=1, H=7, W=9, C=64, G=1), seed=6)
+    finally:
+        dcn.dcnv4_set_option(opt, 0 if opt != "xcd_remap" else 1)
+
+
+# ------------------------------------------------------------------ degenerate inputs
+def test_everything_outside_gives_zero_and_absurd_offsets_are_safe():
+    cfg = Config("oob", N=2, H=9, W=10, C=32, G=2)
+    for dtype in ("f32", "f16"):
+        t = make_inputs(cfg, dtype, seed=7)
+        t["offset"] = np.where(t["offset"] > 0, 60.0, -60.0).astype(t["offset"].dtype)
+        assert check_forward(cfg, dtype, inputs=t) == 0.0
+    t = make_inputs(cfg, "f32", seed=7)
+    sel = np.random.default_rng(0).random(t["offset"].shape) < 0.3
+    t["offset"] = np.where(sel, np.float32(3e30) * np.sign(t["offset"]), t["offset"]).astype(np.float32)
+    check_forward(cfg, "f32", inputs=t)
+    check_backward(cfg, inputs=t)
+    t = make_inputs(cfg, "f16", seed=7)
+    t["offset"] = np.where(sel, np.float16(65504.0) * np.sign(t["offset"]), t["offset"]).astype(np.float16)
+    check_forward(cfg, "f16", inputs=t)
+
+
+def test_exact_integer_offsets_and_image_border_kinks():
+    """Whole-number offsets (also landing exactly on row/column -1 and H/W) follow the floor rule."""
+    cfg = Config("ints", N=2, H=8, W=7, C=32, G=2, sigma=3.0)
+    t = make_inputs(cfg, "f32", seed=8, integer_fraction=1.0)
+    assert np.all(t["offset"] == np.round(t["offset"]))
+    check_forward(cfg, "f32", inputs=t)
+    check_backward(cfg, inputs=t)
+
+
+def test_whole_pixel_shift_is_bit_exact_on_gpu():
+    N, H, W, G, Cg = 1, 9, 8, 2, 16
+    rng = np.random.default_rng(9)
+    for dtype in ("f32", "f16"):
+        npdt = np.float32 if dtype == "f32" else np.float16
+        x = rng.standard_normal((N, H, W, G * Cg)).astype(npdt)
+        off = rng.standard_normal((N, H, W, G, 9, 2)).astype(npdt)
+        m = np.zeros((N, H, W, G, 9), dtype=npdt)
+        i, j, dx, dy = 2, 0, -2, 1
+        k = j * 3 + i
+        off[..., k, 0], off[..., k, 1], m[..., k] = dx, dy, 1.0
+        d = to_gpu(dict(x=x, offset=off, mask=m), dtype)
+        y = dcn.dcnv4_forward(d["x"], d["offset"], d["mask"]).cpu().numpy()
+        ref = np.zeros_like(x)
+        for h in range(H):
+            for w in range(W):
+                hs, ws = h + i - 1 + dy, w + j - 1 + dx
+                if 0 <= hs < H and 0 <= ws < W:
+                    ref[0, h, w] = x[0, hs, ws]
+        np.testing.assert_array_equal(y, ref)
+
+
+def test_backward_twice_agrees_within_tolerance():
+    """grad_x is summed with atomics, so the order of additions can differ between runs."""
+    cfg = CONFIGS["c1"]
+    t = make_inputs(cfg, "f32", seed=0)
+    d = to_gpu(t, "f32")
+    a = dcn.dcnv4_backward(d["x"], d["offset"], d["mask"], d["grad_y"])
+    b = dcn.dcnv4_backward(d["x"], d["offset"], d["mask"], d["grad_y"])
+    torch.cuda.synchronize()
+    for u, v in zip(a, b):
+        close("rerun", u.cpu().numpy(), v.cpu().numpy().astype(np.float64), 1e-5)
+    assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])      # no atomics in these two
+
+
+def test_runs_on_a_side_stream():
+    cfg = Config("stream", N=2, H=12, W=12, C=64, G=4)
+    t = make_inputs(cfg, "f16", seed=10)
+    d = to_gpu(t, "f16")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    y = dcn.dcnv4_forward(d["x"], d["offset"], d["mask"], stream=s)
+    s.synchronize()
+    ref = oracle.forward(t["x"], t["offset"], t["mask"])
+    close("stream/y", y.cpu().numpy(), ref, TOL["f16"])
+
+
+def test_gpu_call_with_bad_arguments_returns_error_and_writes_nothing():
+    cfg = Config("bad", N=1, H=8, W=8, C=32, G=2)
+    d = to_gpu(make_inputs(cfg, "f32", seed=11), "f32")
+    y = torch.full((1, 8, 8, 32), 5.0, device="cuda")
+    with pytest.raises(dcn.Dcnv4Error) as e:                                 # 5x5 window: outside the supported set
+        dcn.dcnv4_forward(d["x"], d["x"].new_zeros((1, 6, 6, 2, 25, 2)), d["x"].new_zeros((1, 6, 6, 2, 25)),
+                          kernel=5, out=y[:, :6, :6].contiguous())
+    assert e.value.status == 3
+    with pytest.raises(dcn.Dcnv4Error):
+        h = {k: v.half() for k, v in d.items()}
+        dcn.dcnv4_backward(h["x"], h["offset"], h["mask"], h["grad_y"])       # fp16 backward is not offered
+    torch.cuda.synchronize()
+    assert torch.all(y == 5.0)
