@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
+                    help="library tuning option (dcnv4_set_option), repeatable")
     return ap.parse_args()
 
 
@@ -72,6 +74,9 @@ def main():
     import torch
     dcn = ensure_built()
     lib = dcn.load_library()
+    for kv in a.opt:
+        k, v = kv.split("=")
+        dcn.dcnv4_set_option(k, int(v))
     from paper_2401_06197_amd.synth import CONFIGS, make_inputs
 
     if not torch.cuda.is_available():
@@ -118,7 +123,7 @@ def main():
         steps = a.steps if direction == "fwd" else max(1, a.steps // 4)
         t = time_leg(torch, stream, launch, a.sets, steps, a.warmup)
         legs[leg] = {
-            "kernel": dcn.dcnv4_kernel_name(direction == "bwd", code, cfg.Cg),
+            "kernel": dcn.dcnv4_last_kernel_name(direction == "bwd"),
             "steps": steps,
             "us_per_launch": round(t["cold"] * 1e3, 3),
             "out_elems_per_s": out_elems / (t["cold"] * 1e-3),

@@ -88,16 +88,23 @@ long long dcnv4_forward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
 long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
                                            int H_out, int W_out, int dtype);
 
-/* Tuning knobs for benchmarking (process-wide, not thread-safe).  Keys:
- *   "fwd_cpt"  channels per thread in the forward kernel (8 or 16; 0 = library default)
- *   "bwd_cpt"  channels per thread in the backward kernel (4, 8 or 16; 0 = default)
- *   "xcd_remap" 1 = hand consecutive tiles to one XCD (default), 0 = plain block order
+/* Tuning knobs for benchmarking (process-wide, not thread-safe); value 0 restores the default.
+ *   "fwd_path"    1 = direct global gather, 2 = input window staged in LDS, 0 = staged where a
+ *                 useful tile fits, else direct
+ *   "halo"        displacement in pixels that the staged window allows for (default 6);
+ *                 samples beyond it are still exact, they take the global path
+ *   "lds_kb"      LDS budget per workgroup of the staged kernel (8..160)
+ *   "fwd_threads" workgroup size of the staged kernel (256 or 512)
+ *   "fwd_cpt"     channels per thread in the direct forward kernel (8 or 16)
+ *   "bwd_cpt"     channels per thread in the backward kernel (4, 8 or 16)
+ *   "xcd_remap"   1 = hand consecutive tiles to one XCD (default), 0 = plain block order
  * Returns DCNV4_ERR_UNSUPPORTED for an unknown key or value. */
 int dcnv4_set_option(const char *key, int value);
 
-/* Name of the forward / backward kernel the current options select for (dtype, Cg),
- * as it appears in a profiler's kernel trace.  Static storage; NULL if unsupported. */
-const char *dcnv4_kernel_name(int backward, int dtype, int Cg);
+/* Name of the kernel that the most recent dcnv4_forward (backward = 0) or dcnv4_backward
+ * (backward = 1) call launched, as it appears in a profiler's kernel trace.  Static storage;
+ * NULL before the first such call. */
+const char *dcnv4_last_kernel_name(int backward);
 
 const char *dcnv4_status_string(int status);
 

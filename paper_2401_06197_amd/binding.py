@@ -17,7 +17,7 @@ DCNV4_OK = 0
 EXPORTS = (
     "dcnv4_output_hw", "dcnv4_forward", "dcnv4_backward",
     "dcnv4_forward_algorithmic_bytes", "dcnv4_backward_algorithmic_bytes",
-    "dcnv4_set_option", "dcnv4_kernel_name", "dcnv4_status_string",
+    "dcnv4_set_option", "dcnv4_last_kernel_name", "dcnv4_status_string",
 )
 
 _lib = None
@@ -53,8 +53,8 @@ def load_library():
         f.restype = ctypes.c_longlong
     lib.dcnv4_set_option.argtypes = [ctypes.c_char_p, ci]
     lib.dcnv4_set_option.restype = ci
-    lib.dcnv4_kernel_name.argtypes = [ci, ci, ci]
-    lib.dcnv4_kernel_name.restype = ctypes.c_char_p
+    lib.dcnv4_last_kernel_name.argtypes = [ci]
+    lib.dcnv4_last_kernel_name.restype = ctypes.c_char_p
     lib.dcnv4_status_string.argtypes = [ci]
     lib.dcnv4_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -84,8 +84,8 @@ def dcnv4_set_option(key, value):
         raise Dcnv4Error(rc, f"dcnv4_set_option({key!r}, {value})")
 
 
-def dcnv4_kernel_name(backward, dtype, Cg):
-    s = load_library().dcnv4_kernel_name(int(backward), int(dtype), int(Cg))
+def dcnv4_last_kernel_name(backward):
+    s = load_library().dcnv4_last_kernel_name(int(backward))
     return s.decode() if s else None
 
 

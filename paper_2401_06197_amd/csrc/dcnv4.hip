@@ -69,15 +69,18 @@ __device__ __forceinline__ int tile_of_block(const Geo &p)
 }
 
 // Copy `bytes` of a tensor region starting at byte `start` (of `base`, 16-byte aligned) into
-// LDS, beginning at the 16-byte boundary below `start`; returns through `delta` how many
-// bytes of lead-in precede the region in LDS.  All global reads are aligned 128-bit loads;
-// the descriptor ends exactly at the region's end, so nothing past the tensor is touched.
-template <int CAP_BYTES>
+// LDS, beginning at the 16-byte boundary below `start`; returns how many bytes of lead-in
+// precede the region in LDS.  All global reads are aligned 128-bit loads whose dwords are
+// range-checked one by one against a descriptor that ends exactly at the region's end, so
+// nothing past the tensor is touched.  A region of 2-byte elements can end in the middle of a
+// dword; the hardware zeroes that whole dword, so the thread that holds it fetches the last
+// element again with a 16-bit load.
+template <int CAP_BYTES, int ELEM_BYTES>
 __device__ __forceinline__ int stage_region(char *lds, const char *base, long long start, int bytes)
 {
     const long long aligned = start & ~15LL;
     const int delta = (int)(start - aligned);
-    const int total = delta + bytes;                       // <= CAP_BYTES by construction
+    const int total = delta + bytes;                       // < CAP_BYTES by construction
     const rsrc_t r = make_rsrc(base + aligned, (unsigned)total);
 #pragma unroll
     for (int o = 0; o < CAP_BYTES; o += kThreads * 16) {
@@ -85,6 +88,10 @@ __device__ __forceinline__ int stage_region(char *lds, const char *base, long lo
         if (off < total) {
             const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
             *reinterpret_cast<u32x4 *>(lds + off) = v;
+            if (ELEM_BYTES == 2 && (total & 2) && off + 16 >= total) {
+                const unsigned short tail = __builtin_amdgcn_raw_buffer_load_b16(r, total - 2, 0, 0);
+                *reinterpret_cast<unsigned short *>(lds + total - 2) = tail;
+            }
         }
     }
     return delta;
@@ -144,26 +151,62 @@ struct Tap {
     int o00, o01, o10, o11;
 };
 
-__device__ __forceinline__ Tap tap_geometry(float dY, float dX, int base_h, int base_w, int chan_bytes,
-                                            const Geo &p)
+// Byte offsets of the 4 neighbours of a sampling position given as whole-pixel window origin
+// (base_h, base_w) plus the already scaled displacement (dy, dx).
+__device__ __forceinline__ Tap tap_offsets(float dy, float dx, int base_h, int base_w, int chan_bytes, float dmax,
+                                           int W, int row_bytes, int pix_bytes)
 {
     // The whole-pixel part of the sampling position is kept in integers and only the scaled
     // offset goes through fp32, so the fractional parts carry no error from the magnitude of
-    // the pixel coordinate.
-    float dy = __builtin_fminf(__builtin_fmaxf(p.scale * dY, -p.dmax), p.dmax);
-    float dx = __builtin_fminf(__builtin_fmaxf(p.scale * dX, -p.dmax), p.dmax);
+    // the pixel coordinate.  Beyond +-dmax every neighbour is outside, so clamping changes nothing.
+    dy = __builtin_fminf(__builtin_fmaxf(dy, -dmax), dmax);
+    dx = __builtin_fminf(__builtin_fmaxf(dx, -dmax), dmax);
     const float fy = __builtin_floorf(dy), fx = __builtin_floorf(dx);
     Tap t;
     t.lh = dy - fy;
     t.lw = dx - fx;
     const int h0 = base_h + (int)fy, w0 = base_w + (int)fx;
-    const int o = h0 * p.row_bytes + w0 * p.pix_bytes + chan_bytes;
-    const bool in0 = (unsigned)w0 < (unsigned)p.W, in1 = (unsigned)(w0 + 1) < (unsigned)p.W;
+    const int o = h0 * row_bytes + w0 * pix_bytes + chan_bytes;
+    const bool in0 = (unsigned)w0 < (unsigned)W, in1 = (unsigned)(w0 + 1) < (unsigned)W;
     t.o00 = in0 ? o : kOutside;
-    t.o10 = in0 ? o + p.row_bytes : kOutside;
-    t.o01 = in1 ? o + p.pix_bytes : kOutside;
-    t.o11 = in1 ? o + p.row_bytes + p.pix_bytes : kOutside;
+    t.o10 = in0 ? o + row_bytes : kOutside;
+    t.o01 = in1 ? o + pix_bytes : kOutside;
+    t.o11 = in1 ? o + row_bytes + pix_bytes : kOutside;
     return t;
+}
+
+__device__ __forceinline__ Tap tap_geometry(float dY, float dX, int base_h, int base_w, int chan_bytes,
+                                            const Geo &p)
+{
+    return tap_offsets(p.scale * dY, p.scale * dX, base_h, base_w, chan_bytes, p.dmax, p.W, p.row_bytes,
+                       p.pix_bytes);
+}
+
+// channel c of a 16-byte unit, widened to fp32
+template <typename T> __device__ __forceinline__ float unit_get(const u32x4 &v, int c);
+template <> __device__ __forceinline__ float unit_get<_Float16>(const u32x4 &v, int c)
+{
+    return (float)__builtin_bit_cast(f16x8, v)[c];
+}
+template <> __device__ __forceinline__ float unit_get<float>(const u32x4 &v, int c)
+{
+    return __builtin_bit_cast(f32x4, v)[c];
+}
+
+// store one 16-byte unit of results (8 fp16 or 4 fp32 values, one rounding to nearest even)
+template <typename T> __device__ __forceinline__ void store_unit(rsrc_t r, int off, const float *a);
+template <> __device__ __forceinline__ void store_unit<_Float16>(rsrc_t r, int off, const float *a)
+{
+    f16x8 h;
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+        h[c] = (_Float16)a[c];
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, h), r, off, 0, 0);
+}
+template <> __device__ __forceinline__ void store_unit<float>(rsrc_t r, int off, const float *a)
+{
+    f32x4 f = {a[0], a[1], a[2], a[3]};
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, f), r, off, 0, 0);
 }
 
 // Shared per-thread decode: which (pixel, group, channel run) this thread serves.
@@ -215,9 +258,9 @@ __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict
     const Item it = decode_item<TPG>(p, tile);
 
     const long long pg_first = (long long)it.n * p.pgi + it.pg0;
-    const int d_off = stage_region<OFF_CAP>(s_off, (const char *)offset, pg_first * (2 * kTaps * (int)sizeof(T)),
+    const int d_off = stage_region<OFF_CAP, (int)sizeof(T)>(s_off, (const char *)offset, pg_first * (2 * kTaps * (int)sizeof(T)),
                                             it.npg * 2 * kTaps * (int)sizeof(T));
-    const int d_msk = stage_region<MSK_CAP>(s_msk, (const char *)mask, pg_first * (kTaps * (int)sizeof(T)),
+    const int d_msk = stage_region<MSK_CAP, (int)sizeof(T)>(s_msk, (const char *)mask, pg_first * (kTaps * (int)sizeof(T)),
                                             it.npg * kTaps * (int)sizeof(T));
     __syncthreads();
     if (!it.active)
@@ -265,6 +308,8 @@ __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict
     store_run<CPT>(ry, it.pix * p.pix_bytes + chan_bytes, acc, (T *)nullptr);
 }
 
+#include "dcnv4_fwd_tiled.inc"
+
 // ------------------------------------------------------------------------------------------
 // Backward (chain rule on Eq. 1), fp32.  Same thread organisation as the forward.  The
 // per-channel products are reduced inside the thread; when a group is split over TPG lanes
@@ -311,9 +356,9 @@ __global__ __launch_bounds__(kThreads) void dcnv4_bwd_kernel(const float *__rest
     const Item it = decode_item<TPG>(p, tile);
 
     const long long pg_first = (long long)it.n * p.pgi + it.pg0;
-    const int d_off = stage_region<OFF_CAP>(s_off, (const char *)offset, pg_first * (2 * kTaps * (int)sizeof(T)),
+    const int d_off = stage_region<OFF_CAP, (int)sizeof(T)>(s_off, (const char *)offset, pg_first * (2 * kTaps * (int)sizeof(T)),
                                             it.npg * 2 * kTaps * (int)sizeof(T));
-    const int d_msk = stage_region<MSK_CAP>(s_msk, (const char *)mask, pg_first * (kTaps * (int)sizeof(T)),
+    const int d_msk = stage_region<MSK_CAP, (int)sizeof(T)>(s_msk, (const char *)mask, pg_first * (kTaps * (int)sizeof(T)),
                                             it.npg * kTaps * (int)sizeof(T));
     __syncthreads();
 
@@ -400,7 +445,13 @@ namespace {
 
 struct Options {
     int fwd_cpt = 0, bwd_cpt = 0, xcd_remap = 1;
+    int fwd_path = 0;      // 0 auto, 1 direct global gather, 2 LDS-tiled
+    int halo = 0;          // 0 = default
+    int lds_kb = 0;        // LDS budget per workgroup of the tiled kernel, 0 = default
+    int fwd_threads = 0;   // 256 or 512 for the tiled kernel, 0 = default
 } g_opt;
+
+char g_last_kernel[2][96];
 
 FastDiv make_div(unsigned d)
 {
@@ -523,6 +574,8 @@ int launch_fwd(const void *x, const void *off, const void *msk, void *y, const P
         return rc;
     hipLaunchKernelGGL((dcnv4_fwd_kernel<T, CG, CPT>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const T *)x,
                        (const T *)off, (const T *)msk, (T *)y, p);
+    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_fwd_kernel<%s, %d, %d>",
+             sizeof(T) == 2 ? "_Float16" : "float", CG, CPT);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
 }
 
@@ -539,9 +592,147 @@ int dispatch_fwd_cpt(int cpt, const void *x, const void *off, const void *msk, v
     return DCNV4_ERR_UNSUPPORTED;
 }
 
+
+constexpr int kDefaultHalo = 6;
+constexpr int kDefaultLdsKb = 78;
+constexpr int kMaxLdsBytes = 160 * 1024;
+
+// Tile choice for the LDS-staged forward: full-width row bands when a band with a useful
+// number of rows fits the LDS budget, otherwise split the columns too.  Returns false when
+// no tile with at least as many output rows/cols as the halo fits (the rectangle would be
+// mostly halo); the caller then uses the direct kernel.
+bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, TGeo *out)
+{
+    const int es = esize(q.dtype), pb = q.Cg * es;
+    const int stage = (threads / 64) * 64 * 27 * es;
+    const long long budget_px = ((long long)lds_bytes - stage) / pb;
+    if (budget_px < 64)
+        return false;
+    const int need = halo > 4 ? halo : 4;
+    for (int kq = 1; kq <= q.Wo; ++kq) {
+        int Q = (q.Wo + kq - 1) / kq;
+        long long cols = (long long)(Q - 1) * q.sw + 2LL * q.dw + 2LL * halo + 2;
+        if (cols > q.W + 2) cols = q.W + 2;
+        const long long rows_max = budget_px / cols;
+        long long R = (rows_max - 2LL * q.dh - 2LL * halo - 2) / q.sh + 1;
+        if (rows_max >= q.H + 2) R = q.Ho;                  // the whole (clipped) height fits
+        if (R > q.Ho) R = q.Ho;
+        if (R < 1 || (R < need && R < q.Ho) || (Q < need && Q < q.Wo))
+            continue;
+        const int kr = (int)((q.Ho + R - 1) / R);
+        R = (q.Ho + kr - 1) / kr;                            // balance the bands
+        long long rows = (R - 1) * q.sh + 2LL * q.dh + 2LL * halo + 2;
+        if (rows > q.H + 2) rows = q.H + 2;
+        out->R = (int)R;
+        out->Q = Q;
+        out->halo = halo;
+        out->pitch = (int)cols;
+        out->tiles_q = (q.Wo + Q - 1) / Q;
+        out->tiles_per_img = kr * out->tiles_q;
+        out->xtile_bytes = (int)(rows * cols * pb);
+        return true;
+    }
+    return false;
+}
+
+int make_tgeo(const Problem &q, int threads, TGeo *out)
+{
+    Geo base;
+    int rc = make_geo(q, 1, &base);          // shares the 32-bit offset validation
+    if (rc)
+        return rc;
+    TGeo p;
+    memset(&p, 0, sizeof(p));
+    const int halo = g_opt.halo ? g_opt.halo : kDefaultHalo;
+    int lds = (g_opt.lds_kb ? g_opt.lds_kb : kDefaultLdsKb) * 1024;
+    if (lds > kMaxLdsBytes) lds = kMaxLdsBytes;
+    if (!choose_tile(q, threads, halo, lds, &p))
+        return DCNV4_ERR_UNSUPPORTED;
+    const long long es = esize(q.dtype);
+    const long long pgi = (long long)q.Ho * q.Wo * q.G;
+    if (pgi >= 0x1000000)                    // offset/mask byte offsets inside one image stay in int32
+        return DCNV4_ERR_UNSUPPORTED;
+    p.H = q.H; p.W = q.W; p.Ho = q.Ho; p.Wo = q.Wo; p.G = q.G;
+    p.sh = q.sh; p.sw = q.sw; p.ph = q.ph; p.pw = q.pw; p.dh = q.dh; p.dw = q.dw;
+    p.scale = q.scale;
+    p.dmax = base.dmax;
+    const long long nblocks = (long long)q.N * p.tiles_per_img * q.G;
+    if (nblocks >= (1LL << 30))
+        return DCNV4_ERR_UNSUPPORTED;
+    p.nblocks = (int)nblocks;
+    p.blocks_per_xcd = (int)((nblocks + kXcds - 1) / kXcds);
+    p.remap = g_opt.xcd_remap;
+    p.div_g = make_div((unsigned)q.G);
+    p.div_tpi = make_div((unsigned)p.tiles_per_img);
+    p.div_tq = make_div((unsigned)p.tiles_q);
+    p.div_q = make_div((unsigned)p.Q);
+    p.div_pitch = make_div((unsigned)p.pitch);
+    p.x_img_bytes = base.x_img_bytes;
+    p.y_img_bytes = base.y_img_bytes;
+    p.row_bytes = base.row_bytes;
+    p.pix_bytes = base.pix_bytes;
+    p.off_img_bytes = (int)(pgi * 18 * es);
+    p.msk_img_bytes = (int)(pgi * 9 * es);
+    *out = p;
+    return DCNV4_OK;
+}
+
+template <typename T, int CG, int THREADS>
+int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    TGeo p;
+    int rc = make_tgeo(q, THREADS, &p);
+    if (rc)
+        return rc;
+    const int lds = p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T);
+    auto kern = dcnv4_fwd_tiled_kernel<T, CG, THREADS>;
+    static int granted = 0;                  // largest dynamic-LDS size already requested for this kernel
+    if (lds > 64 * 1024 && lds > granted) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds) != hipSuccess)
+            return DCNV4_ERR_LAUNCH;
+        granted = lds;
+    }
+    const unsigned grid = (unsigned)(p.remap ? p.blocks_per_xcd * kXcds : p.nblocks);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds, s, (const T *)x, (const T *)off, (const T *)msk, (T *)y,
+                       p);
+    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_fwd_tiled_kernel<%s, %d, %d>",
+             sizeof(T) == 2 ? "_Float16" : "float", CG, THREADS);
+    return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
+// The tiled kernel keeps Cg fp32 accumulators and 4*Cg input values per lane, so it is built
+// for staged pixels of up to 64 bytes.
+template <typename T, int CG>
+int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    if constexpr (CG * sizeof(T) <= 64 && CG * sizeof(T) >= 16) {
+        if (g_opt.fwd_threads == 512)
+            return launch_fwd_tiled<T, CG, 512>(x, off, msk, y, q, s);
+        return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
+    }
+    return DCNV4_ERR_UNSUPPORTED;
+}
+
+template <typename T>
+int dispatch_fwd_tiled_cg(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    switch (q.Cg) {
+    case 8: return dispatch_fwd_tiled<T, 8>(x, off, msk, y, q, s);
+    case 16: return dispatch_fwd_tiled<T, 16>(x, off, msk, y, q, s);
+    case 32: return dispatch_fwd_tiled<T, 32>(x, off, msk, y, q, s);
+    }
+    return DCNV4_ERR_UNSUPPORTED;
+}
+
 template <typename T>
 int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
+    if (g_opt.fwd_path != 1) {
+        const int rc = dispatch_fwd_tiled_cg<T>(x, off, msk, y, q, s);
+        if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 2)
+            return rc;
+    }
     const int cpt = pick_fwd_cpt(q.dtype, q.Cg);
     switch (q.Cg) {
     case 8: return dispatch_fwd_cpt<T, 8>(cpt, x, off, msk, y, q, s);
@@ -567,6 +758,7 @@ int launch_bwd(const void *x, const void *off, const void *msk, const void *gy, 
     hipLaunchKernelGGL((dcnv4_bwd_kernel<CG, CPT>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const float *)x,
                        (const float *)off, (const float *)msk, (const float *)gy, (float *)gx, (float *)go,
                        (float *)gm, p);
+    snprintf(g_last_kernel[1], sizeof(g_last_kernel[1]), "dcnv4_bwd_kernel<%d, %d>", CG, CPT);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
 }
 
@@ -595,8 +787,6 @@ int fill_problem(Problem *q, int N, int H, int W, int G, int Cg, int kh, int kw,
         return DCNV4_ERR_SHAPE;
     return dcnv4_output_hw(H, W, kh, kw, sh, sw, ph, pw, dh, dw, &q->Ho, &q->Wo);
 }
-
-char g_name[96];
 
 }  // namespace
 
@@ -700,24 +890,29 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.xcd_remap = value;
         return DCNV4_OK;
     }
+    if (!strcmp(key, "fwd_path") && value >= 0 && value <= 2) {
+        g_opt.fwd_path = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "halo") && value >= 0 && value <= 64) {
+        g_opt.halo = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "lds_kb") && (value == 0 || (value >= 8 && value <= 160))) {
+        g_opt.lds_kb = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 256 || value == 512)) {
+        g_opt.fwd_threads = value;
+        return DCNV4_OK;
+    }
     return DCNV4_ERR_UNSUPPORTED;
 }
 
-const char *dcnv4_kernel_name(int backward, int dtype, int Cg)
+const char *dcnv4_last_kernel_name(int backward)
 {
-    if (Cg != 8 && Cg != 16 && Cg != 32 && Cg != 64)
-        return nullptr;
-    if (backward) {
-        if (dtype != DCNV4_F32)
-            return nullptr;
-        snprintf(g_name, sizeof(g_name), "dcnv4_bwd_kernel<%d, %d>", Cg, pick_bwd_cpt(Cg));
-    } else {
-        if (dtype != DCNV4_F32 && dtype != DCNV4_F16)
-            return nullptr;
-        snprintf(g_name, sizeof(g_name), "dcnv4_fwd_kernel<%s, %d, %d>", dtype == DCNV4_F16 ? "_Float16" : "float", Cg,
-                 pick_fwd_cpt(dtype, Cg));
-    }
-    return g_name;
+    const char *n = g_last_kernel[backward ? 1 : 0];
+    return n[0] ? n : nullptr;
 }
 
 const char *dcnv4_status_string(int status)

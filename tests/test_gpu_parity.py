@@ -116,15 +116,42 @@ def test_small_geometries_backward(cfg):
     check_backward(cfg, seed=4)
 
 
-@pytest.mark.parametrize("opt,val", [("fwd_cpt", 8), ("fwd_cpt", 16), ("xcd_remap", 0)])
-def test_forward_tuning_variants_agree_with_oracle(opt, val):
+FWD_VARIANTS = [
+    {"fwd_path": 1, "fwd_cpt": 8}, {"fwd_path": 1, "fwd_cpt": 16}, {"fwd_path": 1, "xcd_remap": 0},
+    {"fwd_path": 2}, {"fwd_path": 2, "fwd_threads": 512}, {"fwd_path": 2, "xcd_remap": 0},
+    {"fwd_path": 2, "halo": 1}, {"fwd_path": 2, "halo": 2, "lds_kb": 20}, {"fwd_path": 2, "halo": 12, "lds_kb": 160},
+    {"fwd_path": 2, "halo": 3, "lds_kb": 40, "fwd_threads": 512},
+]
+
+
+@pytest.mark.parametrize("opts", FWD_VARIANTS, ids=[",".join(f"{k}={v}" for k, v in o.items()) for o in FWD_VARIANTS])
+def test_forward_tuning_variants_agree_with_oracle(opts):
+    """Both forward kernels (direct gather; window staged in LDS with its global fallback for
+    far samples) over tile shapes from tiny to whole-image, all against the oracle."""
+    cases = [Config("v", N=3, H=20, W=23, C=64, G=4), Config("v32", N=2, H=11, W=10, C=64, G=2),
+             Config("vs2", N=2, H=21, W=17, C=32, G=2, stride=2, pad=2, dilation=2, sigma=3.0),
+             Config("vwide", N=1, H=9, W=70, C=48, G=3, sigma=5.0)]
+    ran = 0
     try:
-        dcn.dcnv4_set_option(opt, val)
-        for dtype in ("f32", "f16"):
-            check_forward(Config("v", N=3, H=20, W=23, C=64, G=4), dtype, seed=5)
-            check_forward(Config("v32", N=2, H=11, W=10, C=64, G=2), dtype, seed=5)
+        for k, v in opts.items():
+            dcn.dcnv4_set_option(k, v)
+        for cfg in cases:
+            for dtype in ("f32", "f16"):
+                if opts.get("fwd_path") == 2 and cfg.Cg * (2 if dtype == "f16" else 4) > 64:
+                    continue                      # staged kernel is built for pixels of up to 64 bytes
+                try:
+                    check_forward(cfg, dtype, seed=5)
+                except dcn.Dcnv4Error as e:
+                    # forcing the staged kernel is refused when no useful tile fits the LDS budget
+                    assert opts.get("fwd_path") == 2 and e.status == 3
+                    continue
+                ran += 1
+                want = "dcnv4_fwd_tiled_kernel" if opts.get("fwd_path") == 2 else "dcnv4_fwd_kernel"
+                assert dcn.dcnv4_last_kernel_name(0).startswith(want + "<")
+        assert ran >= 1
     finally:
-        dcn.dcnv4_set_option(opt, 0 if opt != "xcd_remap" else 1)
+        for k in opts:
+            dcn.dcnv4_set_option(k, 1 if k == "xcd_remap" else 0)
 
 
 @pytest.mark.parametrize("opt,val", [("bwd_cpt", 4), ("bwd_cpt", 8), ("bwd_cpt", 16), ("xcd_remap", 0)])
