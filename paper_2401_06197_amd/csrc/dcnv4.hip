@@ -593,8 +593,9 @@ int dispatch_fwd_cpt(int cpt, const void *x, const void *off, const void *msk, v
 }
 
 
+constexpr int kTiledExtraLds = 128;         // two staged pixels of zeros
 constexpr int kDefaultHalo = 6;
-constexpr int kDefaultLdsKb = 78;
+constexpr int kDefaultLdsKb = 158;
 constexpr int kMaxLdsBytes = 160 * 1024;
 
 // Tile choice for the LDS-staged forward: full-width row bands when a band with a useful
@@ -604,8 +605,9 @@ constexpr int kMaxLdsBytes = 160 * 1024;
 bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, TGeo *out)
 {
     const int es = esize(q.dtype), pb = q.Cg * es;
-    const int stage = (threads / 64) * 64 * 27 * es;
-    const long long budget_px = ((long long)lds_bytes - stage) / pb;
+    const int stage = (threads / 64) * 64 * 27 * es + kTiledExtraLds;
+    // two rectangle buffers share what the per-wave slices leave; each is a multiple of 1 KiB
+    const long long budget_px = ((((long long)lds_bytes - stage) / 2) & ~1023LL) / pb;
     if (budget_px < 64)
         return false;
     const int need = halo > 4 ? halo : 4;
@@ -629,7 +631,7 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, TGeo *o
         out->pitch = (int)cols;
         out->tiles_q = (q.Wo + Q - 1) / Q;
         out->tiles_per_img = kr * out->tiles_q;
-        out->xtile_bytes = (int)(rows * cols * pb);
+        out->xtile_bytes = (int)((rows * cols * pb + 1023) & ~1023LL);
         return true;
     }
     return false;
@@ -684,7 +686,7 @@ int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, c
     int rc = make_tgeo(q, THREADS, &p);
     if (rc)
         return rc;
-    const int lds = p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T);
+    const int lds = 2 * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) + kTiledExtraLds;
     auto kern = dcnv4_fwd_tiled_kernel<T, CG, THREADS>;
     static int granted = 0;                  // largest dynamic-LDS size already requested for this kernel
     if (lds > 64 * 1024 && lds > granted) {
@@ -693,7 +695,22 @@ int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, c
             return DCNV4_ERR_LAUNCH;
         granted = lds;
     }
-    const unsigned grid = (unsigned)(p.remap ? p.blocks_per_xcd * kXcds : p.nblocks);
+    // persistent workgroups: one per compute unit (or fewer when there are fewer tiles)
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
+            return DCNV4_ERR_LAUNCH;
+        cus = n;
+    }
+    unsigned grid;
+    if (p.remap) {
+        const int per = cus / kXcds < p.blocks_per_xcd ? cus / kXcds : p.blocks_per_xcd;
+        grid = (unsigned)(per * kXcds);
+    } else {
+        grid = (unsigned)(cus < p.nblocks ? cus : p.nblocks);
+    }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds, s, (const T *)x, (const T *)off, (const T *)msk, (T *)y,
                        p);
     snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_fwd_tiled_kernel<%s, %d, %d>",
@@ -707,9 +724,13 @@ template <typename T, int CG>
 int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
     if constexpr (CG * sizeof(T) <= 64 && CG * sizeof(T) >= 16) {
-        if (g_opt.fwd_threads == 512)
+        // 64-byte pixels need more registers per lane than eight waves per workgroup leave
+        if (g_opt.fwd_threads == 256 || (g_opt.fwd_threads == 0 && CG * sizeof(T) == 64))
+            return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
+        if constexpr (CG * sizeof(T) < 64)
             return launch_fwd_tiled<T, CG, 512>(x, off, msk, y, q, s);
-        return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
+        else
+            return DCNV4_ERR_UNSUPPORTED;
     }
     return DCNV4_ERR_UNSUPPORTED;
 }
