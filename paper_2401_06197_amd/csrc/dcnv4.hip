@@ -593,7 +593,8 @@ int dispatch_fwd_cpt(int cpt, const void *x, const void *off, const void *msk, v
 }
 
 
-constexpr int kTiledExtraLds = 128;         // two staged pixels of zeros
+// (pitch + 2) staged pixels of zeros follow the slices; the chooser reserves room for the widest pitch
+constexpr int kTiledZeroPixelsExtra = 2;
 constexpr int kDefaultHalo = 6;
 constexpr int kDefaultLdsKb = 158;
 constexpr int kMaxLdsBytes = 160 * 1024;
@@ -605,32 +606,58 @@ constexpr int kMaxLdsBytes = 160 * 1024;
 bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, TGeo *out)
 {
     const int es = esize(q.dtype), pb = q.Cg * es;
-    const int stage = (threads / 64) * 64 * 27 * es + kTiledExtraLds;
-    // two rectangle buffers share what the per-wave slices leave; each is a multiple of 1 KiB
-    const long long budget_px = ((((long long)lds_bytes - stage) / 2) & ~1023LL) / pb;
-    if (budget_px < 64)
-        return false;
+    const int slices = (threads / 64) * 64 * 27 * es;
     const int need = halo > 4 ? halo : 4;
+    const int waves = threads / 64;
     for (int kq = 1; kq <= q.Wo; ++kq) {
-        int Q = (q.Wo + kq - 1) / kq;
+        const int Q = (q.Wo + kq - 1) / kq;
         long long cols = (long long)(Q - 1) * q.sw + 2LL * q.dw + 2LL * halo + 2;
-        if (cols > q.W + 2) cols = q.W + 2;
-        const long long rows_max = budget_px / cols;
-        long long R = (rows_max - 2LL * q.dh - 2LL * halo - 2) / q.sh + 1;
-        if (rows_max >= q.H + 2) R = q.Ho;                  // the whole (clipped) height fits
-        if (R > q.Ho) R = q.Ho;
-        if (R < 1 || (R < need && R < q.Ho) || (Q < need && Q < q.Wo))
+        if (cols > q.W + 4) cols = q.W + 4;
+        // two rectangle buffers (each a multiple of 1 KiB) share what the slices and the zero block leave
+        const long long zero_bytes = (cols + kTiledZeroPixelsExtra) * pb;
+        const long long budget_px = ((((long long)lds_bytes - slices - zero_bytes) / 2) & ~1023LL) / pb;
+        if (budget_px < 64)
             continue;
+        const long long rows_max = budget_px / cols;
+        long long Rmax = (rows_max - 2LL * q.dh - 2LL * halo - 2) / q.sh + 1;
+        if (rows_max >= q.H + 4) Rmax = q.Ho;               // the whole (clipped) height fits
+        if (Rmax > q.Ho) Rmax = q.Ho;
+        if (Rmax < 1 || (Rmax < need && Rmax < q.Ho) || (Q < need && Q < q.Wo))
+            continue;
+        // Among the band heights that fit, take the one that wastes the fewest wave slots: a tile
+        // of B batches (64 output pixels each) keeps the workgroup busy for ceil(B / waves) rounds,
+        // and every tile also costs a barrier and a drained pipeline (measured: about four rounds).
+        const int tiles_q = (q.Wo + Q - 1) / Q;
+        const int Qlast = q.Wo - (tiles_q - 1) * Q;
+        long long best_R = Rmax;
+        double best_cost = 1e30;
+        const long long Rlow = Rmax < need ? Rmax : need;
+        for (long long R = Rmax; R >= Rlow; --R) {
+            const long long bands = (q.Ho + R - 1) / R, Rlast = q.Ho - (bands - 1) * R;
+            double cost = 0;
+            for (int lastq = 0; lastq < 2; ++lastq) {
+                const long long nq = lastq ? 1 : tiles_q - 1;      // tiles of this width per band
+                if (nq == 0) continue;
+                (void)Qlast;                                        // narrower last column still walks R x Q slots
+                const long long b_full = (R * Q + 63) / 64, b_last = (Rlast * Q + 63) / 64;
+                cost += nq * ((bands - 1) * (double)((b_full + waves - 1) / waves) +
+                              (double)((b_last + waves - 1) / waves) + 4.0 * bands);
+            }
+            if (cost < best_cost - 1e-9) {
+                best_cost = cost;
+                best_R = R;
+            }
+        }
+        const long long R = best_R;
         const int kr = (int)((q.Ho + R - 1) / R);
-        R = (q.Ho + kr - 1) / kr;                            // balance the bands
         long long rows = (R - 1) * q.sh + 2LL * q.dh + 2LL * halo + 2;
-        if (rows > q.H + 2) rows = q.H + 2;
+        if (rows > q.H + 4) rows = q.H + 4;
         out->R = (int)R;
         out->Q = Q;
         out->halo = halo;
         out->pitch = (int)cols;
-        out->tiles_q = (q.Wo + Q - 1) / Q;
-        out->tiles_per_img = kr * out->tiles_q;
+        out->tiles_q = tiles_q;
+        out->tiles_per_img = kr * tiles_q;
         out->xtile_bytes = (int)((rows * cols * pb + 1023) & ~1023LL);
         return true;
     }
@@ -686,7 +713,8 @@ int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, c
     int rc = make_tgeo(q, THREADS, &p);
     if (rc)
         return rc;
-    const int lds = 2 * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) + kTiledExtraLds;
+    const int lds = 2 * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) +
+                    (p.pitch + kTiledZeroPixelsExtra) * CG * (int)sizeof(T);
     auto kern = dcnv4_fwd_tiled_kernel<T, CG, THREADS>;
     static int granted = 0;                  // largest dynamic-LDS size already requested for this kernel
     if (lds > 64 * 1024 && lds > granted) {
@@ -935,6 +963,13 @@ const char *dcnv4_last_kernel_name(int backward)
     const char *n = g_last_kernel[backward ? 1 : 0];
     return n[0] ? n : nullptr;
 }
+
+#ifdef DCNV4_TRACE
+int dcnv4_debug_read_trace(void *dst, size_t bytes)
+{
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_dcnv4_trace), bytes < sizeof(g_dcnv4_trace) ? bytes : sizeof(g_dcnv4_trace));
+}
+#endif
 
 const char *dcnv4_status_string(int status)
 {
