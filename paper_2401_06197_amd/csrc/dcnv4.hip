@@ -545,8 +545,8 @@ unsigned grid_of(const Geo &p) { return (unsigned)(p.remap ? p.tiles_per_xcd * k
 
 int default_fwd_cpt(int dtype, int Cg)
 {
-    if (Cg == 8) return 8;
-    return dtype == DCNV4_F16 ? 16 : 8;
+    (void)dtype;
+    return Cg == 8 ? 8 : 8;      // 16-byte (fp16) or 32-byte (fp32) runs per lane: neighbouring lanes share cache lines
 }
 int default_bwd_cpt(int Cg) { return Cg == 8 ? 8 : 8; }
 
@@ -713,6 +713,10 @@ int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, c
     int rc = make_tgeo(q, THREADS, &p);
     if (rc)
         return rc;
+    // a tile of one or two 64-pixel batches leaves most of the workgroup's waves idle and pays the
+    // tile switch for almost no work: such images are left to the direct kernel unless forced
+    if (g_opt.fwd_path != 2 && p.R * p.Q < 128)
+        return DCNV4_ERR_UNSUPPORTED;
     const int lds = 2 * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) +
                     (p.pitch + kTiledZeroPixelsExtra) * CG * (int)sizeof(T);
     auto kern = dcnv4_fwd_tiled_kernel<T, CG, THREADS>;
