@@ -308,7 +308,7 @@ __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict
     store_run<CPT>(ry, it.pix * p.pix_bytes + chan_bytes, acc, (T *)nullptr);
 }
 
-#include "dcnv4_fwd_tiled.inc"
+#include "dcnv4_tiled.inc"
 
 // ------------------------------------------------------------------------------------------
 // Backward (chain rule on Eq. 1), fp32.  Same thread organisation as the forward.  The
@@ -449,6 +449,7 @@ struct Options {
     int halo = 0;          // 0 = default
     int lds_kb = 0;        // LDS budget per workgroup of the tiled kernel, 0 = default
     int fwd_threads = 0;   // 256 or 512 for the tiled kernel, 0 = default
+    int bwd_path = 0;      // 0 auto, 1 direct (global atomics), 2 LDS-tiled
 } g_opt;
 
 char g_last_kernel[2][96];
@@ -603,9 +604,9 @@ constexpr int kMaxLdsBytes = 160 * 1024;
 // number of rows fits the LDS budget, otherwise split the columns too.  Returns false when
 // no tile with at least as many output rows/cols as the halo fits (the rectangle would be
 // mostly halo); the caller then uses the direct kernel.
-bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, TGeo *out)
+bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, TGeo *out)
 {
-    const int es = esize(q.dtype), pb = q.Cg * es;
+    const int es = esize(q.dtype);
     const int slices = (threads / 64) * 64 * 27 * es;
     const int need = halo > 4 ? halo : 4;
     const int waves = threads / 64;
@@ -613,9 +614,9 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, TGeo *o
         const int Q = (q.Wo + kq - 1) / kq;
         long long cols = (long long)(Q - 1) * q.sw + 2LL * q.dw + 2LL * halo + 2;
         if (cols > q.W + 4) cols = q.W + 4;
-        // two rectangle buffers (each a multiple of 1 KiB) share what the slices and the zero block leave
-        const long long zero_bytes = (cols + kTiledZeroPixelsExtra) * pb;
-        const long long budget_px = ((((long long)lds_bytes - slices - zero_bytes) / 2) & ~1023LL) / pb;
+        // the rectangle buffers (each a multiple of 1 KiB) share what the slices and the zero block leave
+        const long long zero_bytes = ((cols + kTiledZeroPixelsExtra) * pb + 15) & ~15LL;
+        const long long budget_px = ((((long long)lds_bytes - slices - zero_bytes) / nbuf) & ~1023LL) / pb;
         if (budget_px < 64)
             continue;
         const long long rows_max = budget_px / cols;
@@ -664,7 +665,8 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, TGeo *o
     return false;
 }
 
-int make_tgeo(const Problem &q, int threads, TGeo *out)
+// `gradx`: geometry for the grad_x kernel, whose single LDS rectangle holds Cg+1 fp32 per pixel.
+int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
 {
     Geo base;
     int rc = make_geo(q, 1, &base);          // shares the 32-bit offset validation
@@ -675,7 +677,7 @@ int make_tgeo(const Problem &q, int threads, TGeo *out)
     const int halo = g_opt.halo ? g_opt.halo : kDefaultHalo;
     int lds = (g_opt.lds_kb ? g_opt.lds_kb : kDefaultLdsKb) * 1024;
     if (lds > kMaxLdsBytes) lds = kMaxLdsBytes;
-    if (!choose_tile(q, threads, halo, lds, &p))
+    if (!choose_tile(q, threads, halo, lds, gradx ? 1 : 2, gradx ? (q.Cg + 1) * 4 : q.Cg * esize(q.dtype), &p))
         return DCNV4_ERR_UNSUPPORTED;
     const long long es = esize(q.dtype);
     const long long pgi = (long long)q.Ho * q.Wo * q.G;
@@ -706,20 +708,25 @@ int make_tgeo(const Problem &q, int threads, TGeo *out)
     return DCNV4_OK;
 }
 
-template <typename T, int CG, int THREADS>
-int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+// Launch of the LDS-staged kernel in one of its modes; `which` = 0 forward, 1 backward (for the
+// kernel-name record).
+template <typename T, int CG, int THREADS, int MODE>
+int launch_tiled(const void *x, const void *off, const void *msk, const void *gy, void *o1, void *o2,
+                 const Problem &q, hipStream_t s, int which)
 {
     TGeo p;
-    int rc = make_tgeo(q, THREADS, &p);
+    constexpr bool kGradX = MODE == kTiledGradX;
+    int rc = make_tgeo(q, THREADS, kGradX, &p);
     if (rc)
         return rc;
     // a tile of one or two 64-pixel batches leaves most of the workgroup's waves idle and pays the
     // tile switch for almost no work: such images are left to the direct kernel unless forced
     if (g_opt.fwd_path != 2 && p.R * p.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
-    const int lds = 2 * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) +
-                    (p.pitch + kTiledZeroPixelsExtra) * CG * (int)sizeof(T);
-    auto kern = dcnv4_fwd_tiled_kernel<T, CG, THREADS>;
+    const int px_bytes = kGradX ? (CG + 1) * 4 : CG * (int)sizeof(T);
+    const int lds = (kGradX ? 1 : 2) * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) +
+                    (((p.pitch + kTiledZeroPixelsExtra) * px_bytes + 15) & ~15);
+    auto kern = dcnv4_tiled_kernel<T, CG, THREADS, MODE>;
     static int granted = 0;                  // largest dynamic-LDS size already requested for this kernel
     if (lds > 64 * 1024 && lds > granted) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -743,11 +750,17 @@ int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, c
     } else {
         grid = (unsigned)(cus < p.nblocks ? cus : p.nblocks);
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds, s, (const T *)x, (const T *)off, (const T *)msk, (T *)y,
-                       p);
-    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_fwd_tiled_kernel<%s, %d, %d>",
-             sizeof(T) == 2 ? "_Float16" : "float", CG, THREADS);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds, s, (const T *)x, (const T *)off, (const T *)msk,
+                       (const T *)gy, (T *)o1, (T *)o2, p);
+    snprintf(g_last_kernel[which], sizeof(g_last_kernel[which]), "dcnv4_tiled_kernel<%s, %d, %d, %d>",
+             sizeof(T) == 2 ? "_Float16" : "float", CG, THREADS, MODE);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
+template <typename T, int CG, int THREADS>
+int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    return launch_tiled<T, CG, THREADS, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0);
 }
 
 // The tiled kernel keeps Cg fp32 accumulators and 4*Cg input values per lane, so it is built
@@ -829,6 +842,38 @@ int dispatch_bwd_cpt(int cpt, const void *x, const void *off, const void *msk, c
     return DCNV4_ERR_UNSUPPORTED;
 }
 
+// Backward through the LDS-staged kernels: zero-fill of grad_x, then the grad_offset/grad_mask
+// pass (gathers, like the forward) and the grad_x pass (LDS-private accumulation, one flush per
+// tile).  Both are validated before anything is launched, so an unsupported shape writes nothing.
+template <int CG>
+int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void *gy, void *gx, void *go, void *gm,
+                     const Problem &q, hipStream_t s)
+{
+    constexpr int THREADS = 256;             // 64-byte pixels: four waves per workgroup
+    TGeo probe;
+    int rc = make_tgeo(q, THREADS, false, &probe);
+    if (rc)
+        return rc;
+    if (g_opt.bwd_path != 2 && probe.R * probe.Q < 128)
+        return DCNV4_ERR_UNSUPPORTED;
+    rc = make_tgeo(q, THREADS, true, &probe);
+    if (rc)
+        return rc;
+    if (g_opt.bwd_path != 2 && probe.R * probe.Q < 128)
+        return DCNV4_ERR_UNSUPPORTED;
+    const long long n16 = (long long)q.N * probe.x_img_bytes / 16;
+    long long zb = (n16 + kThreads - 1) / kThreads;
+    if (zb > 8192) zb = 8192;
+    hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)gx, n16);
+    const int saved = g_opt.fwd_path;
+    g_opt.fwd_path = 2;                      // the size heuristic was applied above
+    rc = launch_tiled<float, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1);
+    if (rc == DCNV4_OK)
+        rc = launch_tiled<float, CG, THREADS, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1);
+    g_opt.fwd_path = saved;
+    return rc;
+}
+
 int fill_problem(Problem *q, int N, int H, int W, int G, int Cg, int kh, int kw, int sh, int sw, int ph, int pw,
                  int dh, int dw, float scale, int dtype)
 {
@@ -903,6 +948,15 @@ int dcnv4_backward(const void *x, const void *offset, const void *mask, const vo
     if (dtype != DCNV4_F32)
         return DCNV4_ERR_UNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
+    if (g_opt.bwd_path != 1) {
+        rc = DCNV4_ERR_UNSUPPORTED;
+        if (Cg == 8)
+            rc = launch_bwd_tiled<8>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+        else if (Cg == 16)
+            rc = launch_bwd_tiled<16>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+        if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.bwd_path == 2)
+            return rc;
+    }
     const int cpt = pick_bwd_cpt(Cg);
     switch (Cg) {
     case 8: return dispatch_bwd_cpt<8>(cpt, x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
@@ -945,6 +999,10 @@ int dcnv4_set_option(const char *key, int value)
     }
     if (!strcmp(key, "fwd_path") && value >= 0 && value <= 2) {
         g_opt.fwd_path = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "bwd_path") && value >= 0 && value <= 2) {
+        g_opt.bwd_path = value;
         return DCNV4_OK;
     }
     if (!strcmp(key, "halo") && value >= 0 && value <= 64) {

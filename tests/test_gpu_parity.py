@@ -146,7 +146,7 @@ def test_forward_tuning_variants_agree_with_oracle(opts):
                     assert opts.get("fwd_path") == 2 and e.status == 3
                     continue
                 ran += 1
-                want = "dcnv4_fwd_tiled_kernel" if opts.get("fwd_path") == 2 else "dcnv4_fwd_kernel"
+                want = "dcnv4_tiled_kernel" if opts.get("fwd_path") == 2 else "dcnv4_fwd_kernel"
                 assert dcn.dcnv4_last_kernel_name(0).startswith(want + "<")
         assert ran >= 1
     finally:
@@ -154,15 +154,40 @@ def test_forward_tuning_variants_agree_with_oracle(opts):
             dcn.dcnv4_set_option(k, 1 if k == "xcd_remap" else 0)
 
 
-@pytest.mark.parametrize("opt,val", [("bwd_cpt", 4), ("bwd_cpt", 8), ("bwd_cpt", 16), ("xcd_remap", 0)])
-def test_backward_tuning_variants_agree_with_oracle(opt, val):
+BWD_VARIANTS = [
+    {"bwd_path": 1, "bwd_cpt": 4}, {"bwd_path": 1, "bwd_cpt": 8}, {"bwd_path": 1, "bwd_cpt": 16},
+    {"bwd_path": 1, "xcd_remap": 0},
+    {"bwd_path": 2}, {"bwd_path": 2, "xcd_remap": 0}, {"bwd_path": 2, "halo": 1}, {"bwd_path": 2, "halo": 3, "lds_kb": 64},
+    {"bwd_path": 2, "halo": 12},
+]
+
+
+@pytest.mark.parametrize("opts", BWD_VARIANTS, ids=[",".join(f"{k}={v}" for k, v in o.items()) for o in BWD_VARIANTS])
+def test_backward_tuning_variants_agree_with_oracle(opts):
+    """Both backward paths (global atomics; LDS-staged gathers plus LDS-private grad_x accumulation
+    with its direct-to-memory pass for far samples) over several tile shapes."""
+    cases = [Config("v", N=3, H=20, W=23, C=64, G=4), Config("v8", N=2, H=11, W=10, C=16, G=2),
+             Config("vs2", N=2, H=21, W=17, C=32, G=2, stride=2, pad=2, dilation=2, sigma=3.0),
+             Config("vwide", N=1, H=9, W=70, C=48, G=3, sigma=5.0), Config("v32", N=2, H=11, W=10, C=64, G=2),
+             Config("v64", N=1, H=7, W=9, C=64, G=1)]
+    ran = 0
     try:
-        dcn.dcnv4_set_option(opt, val)
-        check_backward(Config("v", N=3, H=20, W=23, C=64, G=4), seed=6)
-        check_backward(Config("v32", N=2, H=11, W=10, C=64, G=2), seed=6)
-        check_backward(Config("v64", N=1, H=7, W=9, C=64, G=1), seed=6)
+        for k, v in opts.items():
+            dcn.dcnv4_set_option(k, v)
+        for cfg in cases:
+            try:
+                check_backward(cfg, seed=6)
+            except dcn.Dcnv4Error as e:
+                # forcing the staged kernels is refused for wide groups or when no useful tile fits
+                assert opts.get("bwd_path") == 2 and e.status == 3
+                continue
+            ran += 1
+            want = "dcnv4_tiled_kernel" if opts.get("bwd_path") == 2 else "dcnv4_bwd_kernel"
+            assert dcn.dcnv4_last_kernel_name(1).startswith(want + "<")
+        assert ran >= 3
     finally:
-        dcn.dcnv4_set_option(opt, 0 if opt != "xcd_remap" else 1)
+        for k in opts:
+            dcn.dcnv4_set_option(k, 1 if k == "xcd_remap" else 0)
 
 
 # ------------------------------------------------------------------ degenerate inputs
