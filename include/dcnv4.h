@@ -94,6 +94,7 @@ long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
  *   "bwd_path"    1 = one kernel with global atomics for grad_x, 2 = two LDS-staged kernels (gathers
  *                 for grad_offset/grad_mask; LDS-private accumulation of grad_x), 0 = staged where
  *                 it applies (Cg 8 or 16 and a useful tile fits), else the first
+ *   "gx_threads"  workgroup size of the staged grad_x kernel (256 or 512)
  *   "halo"        displacement in pixels that the staged window allows for (default 6);
  *                 samples beyond it are still exact, they take the global path
  *   "lds_kb"      LDS budget per workgroup of the staged kernel (8..160)

@@ -450,6 +450,7 @@ struct Options {
     int lds_kb = 0;        // LDS budget per workgroup of the tiled kernel, 0 = default
     int fwd_threads = 0;   // 256 or 512 for the tiled kernel, 0 = default
     int bwd_path = 0;      // 0 auto, 1 direct (global atomics), 2 LDS-tiled
+    int gx_threads = 0;    // workgroup size of the grad_x kernel (256 or 512), 0 = default
 } g_opt;
 
 char g_last_kernel[2][96];
@@ -604,7 +605,7 @@ constexpr int kMaxLdsBytes = 160 * 1024;
 // number of rows fits the LDS budget, otherwise split the columns too.  Returns false when
 // no tile with at least as many output rows/cols as the halo fits (the rectangle would be
 // mostly halo); the caller then uses the direct kernel.
-bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, TGeo *out)
+bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, TGeo *out)
 {
     const int es = esize(q.dtype);
     const int slices = (threads / 64) * 64 * 27 * es;
@@ -615,8 +616,10 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
         long long cols = (long long)(Q - 1) * q.sw + 2LL * q.dw + 2LL * halo + 2;
         if (cols > q.W + 4) cols = q.W + 4;
         // the rectangle buffers (each a multiple of 1 KiB) share what the slices and the zero block leave
-        const long long zero_bytes = ((cols + kTiledZeroPixelsExtra) * pb + 15) & ~15LL;
-        const long long budget_px = ((((long long)lds_bytes - slices - zero_bytes) / nbuf) & ~1023LL) / pb;
+        // after the slices: a block of zeros (pitch + 2 pixels), or one lock dword per rectangle pixel
+        const long long zero_bytes = locks ? 16 : ((cols + kTiledZeroPixelsExtra) * pb + 15) & ~15LL;
+        const long long budget_px =
+            ((((long long)lds_bytes - slices - zero_bytes) * pb / (pb + (locks ? 4 : 0)) / nbuf) & ~1023LL) / pb;
         if (budget_px < 64)
             continue;
         const long long rows_max = budget_px / cols;
@@ -677,7 +680,7 @@ int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
     const int halo = g_opt.halo ? g_opt.halo : kDefaultHalo;
     int lds = (g_opt.lds_kb ? g_opt.lds_kb : kDefaultLdsKb) * 1024;
     if (lds > kMaxLdsBytes) lds = kMaxLdsBytes;
-    if (!choose_tile(q, threads, halo, lds, gradx ? 1 : 2, gradx ? (q.Cg + 1) * 4 : q.Cg * esize(q.dtype), &p))
+    if (!choose_tile(q, threads, halo, lds, gradx ? 1 : 2, q.Cg * esize(q.dtype), gradx, &p))
         return DCNV4_ERR_UNSUPPORTED;
     const long long es = esize(q.dtype);
     const long long pgi = (long long)q.Ho * q.Wo * q.G;
@@ -723,9 +726,11 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
     // tile switch for almost no work: such images are left to the direct kernel unless forced
     if (g_opt.fwd_path != 2 && p.R * p.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
-    const int px_bytes = kGradX ? (CG + 1) * 4 : CG * (int)sizeof(T);
-    const int lds = (kGradX ? 1 : 2) * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) +
-                    (((p.pitch + kTiledZeroPixelsExtra) * px_bytes + 15) & ~15);
+    const int px_bytes = CG * (int)sizeof(T);
+    const int tail = kGradX ? (p.xtile_bytes / px_bytes) * 4 + 16 : ((p.pitch + kTiledZeroPixelsExtra) * px_bytes + 15) & ~15;
+    const int lds = (kGradX ? 1 : 2) * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) + tail;
+    if (lds > kMaxLdsBytes)
+        return DCNV4_ERR_UNSUPPORTED;
     auto kern = dcnv4_tiled_kernel<T, CG, THREADS, MODE>;
     static int granted = 0;                  // largest dynamic-LDS size already requested for this kernel
     if (lds > 64 * 1024 && lds > granted) {
@@ -856,7 +861,8 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
         return rc;
     if (g_opt.bwd_path != 2 && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
-    rc = make_tgeo(q, THREADS, true, &probe);
+    const bool gx512 = g_opt.gx_threads == 512;
+    rc = make_tgeo(q, gx512 ? 512 : THREADS, true, &probe);
     if (rc)
         return rc;
     if (g_opt.bwd_path != 2 && probe.R * probe.Q < 128)
@@ -869,7 +875,8 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     g_opt.fwd_path = 2;                      // the size heuristic was applied above
     rc = launch_tiled<float, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1);
     if (rc == DCNV4_OK)
-        rc = launch_tiled<float, CG, THREADS, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1);
+        rc = gx512 ? launch_tiled<float, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1)
+                   : launch_tiled<float, CG, THREADS, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1);
     g_opt.fwd_path = saved;
     return rc;
 }
@@ -999,6 +1006,10 @@ int dcnv4_set_option(const char *key, int value)
     }
     if (!strcmp(key, "fwd_path") && value >= 0 && value <= 2) {
         g_opt.fwd_path = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "gx_threads") && (value == 0 || value == 256 || value == 512)) {
+        g_opt.gx_threads = value;
         return DCNV4_OK;
     }
     if (!strcmp(key, "bwd_path") && value >= 0 && value <= 2) {
