@@ -598,6 +598,7 @@ int dispatch_fwd_cpt(int cpt, const void *x, const void *off, const void *msk, v
 // (pitch + 2) staged pixels of zeros follow the slices; the chooser reserves room for the widest pitch
 constexpr int kTiledZeroPixelsExtra = 2;
 constexpr int kDefaultHalo = 6;
+constexpr int kDefaultHaloGradX = 4;
 constexpr int kDefaultLdsKb = 158;
 constexpr int kMaxLdsBytes = 160 * 1024;
 
@@ -677,7 +678,9 @@ int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
         return rc;
     TGeo p;
     memset(&p, 0, sizeof(p));
-    const int halo = g_opt.halo ? g_opt.halo : kDefaultHalo;
+    // the grad_x kernel sends far samples straight to memory without waiting for them, so it can
+    // afford a tighter rectangle (taller tiles, fewer flushes)
+    const int halo = g_opt.halo ? g_opt.halo : (gradx ? kDefaultHaloGradX : kDefaultHalo);
     int lds = (g_opt.lds_kb ? g_opt.lds_kb : kDefaultLdsKb) * 1024;
     if (lds > kMaxLdsBytes) lds = kMaxLdsBytes;
     if (!choose_tile(q, threads, halo, lds, gradx ? 1 : 2, q.Cg * esize(q.dtype), gradx, &p))
@@ -861,7 +864,7 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
         return rc;
     if (g_opt.bwd_path != 2 && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
-    const bool gx512 = g_opt.gx_threads == 512;
+    const bool gx512 = g_opt.gx_threads != 256;      // eight waves hide the lock round trips better than four
     rc = make_tgeo(q, gx512 ? 512 : THREADS, true, &probe);
     if (rc)
         return rc;
