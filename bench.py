@@ -32,6 +32,10 @@ def parse():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--cold-only", action="store_true", help="skip the back-to-back (hot) timing loop")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a dispatch of known size, for scaling "
+                         "profiler byte counters)")
     ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
                     help="library tuning option (dcnv4_set_option), repeatable")
     return ap.parse_args()
@@ -45,10 +49,26 @@ def ensure_built():
     return binding
 
 
-def time_leg(torch, stream, launch, nsets, steps, warmup):
+def measured_traffic(leg, workload):
+    """HBM bytes per launch of the leg's kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by a copy of known size); read from the committed profile summary, None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"{leg}_{workload}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def time_leg(torch, stream, launch, nsets, steps, warmup, cold_only=False):
     """Average duration of one launch(set_index) in ms: cold (rotating sets) and hot (set 0 only)."""
     out = {}
     for label, pick in (("cold", lambda i: i % nsets), ("hot", lambda i: 0)):
+        if cold_only and label == "hot":
+            out["hot"] = float("nan")
+            continue
         for i in range(warmup):
             launch(pick(i))
         start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -88,6 +108,12 @@ def main():
     dev = torch.device("cuda:0")
     stream = torch.cuda.Stream(device=dev)
     geo = dict(kernel=cfg.kernel, stride=cfg.stride, pad=cfg.pad, dilation=cfg.dilation, offset_scale=cfg.offset_scale)
+    if a.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     legs_wanted = [s for s in a.legs.split(",") if s]
     legs = {}
     host_inputs = {}
@@ -121,7 +147,7 @@ def main():
                 raise dcn.Dcnv4Error(rc, leg)
         torch.cuda.synchronize()
         steps = a.steps if direction == "fwd" else max(1, a.steps // 4)
-        t = time_leg(torch, stream, launch, a.sets, steps, a.warmup)
+        t = time_leg(torch, stream, launch, a.sets, steps, a.warmup, a.cold_only)
         legs[leg] = {
             "kernel": dcn.dcnv4_last_kernel_name(direction == "bwd"),
             "steps": steps,
@@ -130,8 +156,8 @@ def main():
             "algorithmic_bytes": alg,
             "GBps": alg / (t["cold"] * 1e-3) / 1e9,
             "frac_of_hbm_peak": alg / (t["cold"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "hot_us_per_launch": round(t["hot"] * 1e3, 3),
-            "hot_GBps": alg / (t["hot"] * 1e-3) / 1e9,
+            "hot_us_per_launch": None if a.cold_only else round(t["hot"] * 1e3, 3),
+            "hot_GBps": None if a.cold_only else alg / (t["hot"] * 1e-3) / 1e9,
             "buffer_sets": a.sets,
         }
         if leg == legs_wanted[0]:
@@ -142,7 +168,7 @@ def main():
     head = legs_wanted[0]
     hl = legs[head]
     rec = {
-        "metric": "DCNv4 forward output elems/s at 56x56x128 (fp16, N=64); fwd fp32 and bwd fp32 under legs",
+        "metric": "DCNv4 fwd/bwd output elems/s and achieved HBM GB/s (% of peak) at 56x56x128",
         "value": hl["out_elems_per_s"],
         "unit": "output elems/s",
         "n_gpus": 1,
@@ -157,7 +183,7 @@ def main():
         "config": {"workload": f"{cfg.name}: N={cfg.N} {cfg.H}x{cfg.W} C={cfg.C} G={cfg.G} 3x3 s1 p1, leg {head}",
                    "offset_std_px": cfg.sigma, "cache": "cold (rotating buffer sets)"},
         "roofline": {"bound": "hbm", "kernel": hl["kernel"], "achieved": hl["GBps"], "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": hl["frac_of_hbm_peak"], "traffic": None},
+                     "unit": "GB/s", "frac": hl["frac_of_hbm_peak"], "traffic": measured_traffic(head, cfg.name)},
         "legs": legs,
     }
 
@@ -165,7 +191,7 @@ def main():
         import oracle
         t = host_inputs[head.split("_")[1]]
         reps, spent, ref = 0, 0.0, None
-        while spent < a.cpu_seconds and reps < 20:
+        while spent < a.cpu_seconds and reps < 40:
             t0 = time.perf_counter()
             ref = oracle.forward(t["x"], t["offset"], t["mask"], **geo)
             spent += time.perf_counter() - t0

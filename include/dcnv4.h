@@ -20,14 +20,17 @@
  *   offset, grad_offset  [N, Ho, Wo, G, 9, 2]
  *   mask, grad_mask      [N, Ho, Wo, G, 9]
  *   y, grad_y            [N, Ho, Wo, G*Cg]
- * with (Ho, Wo) as returned by dcnv4_output_hw().  The library keeps no state,
- * allocates nothing, enqueues its kernels on `stream` (a hipStream_t, NULL = the
- * default stream) and returns without synchronising.  Outputs must not alias inputs.
+ * with (Ho, Wo) as returned by dcnv4_output_hw().  The library allocates nothing and
+ * keeps nothing between calls except the tuning options below; it enqueues its kernels
+ * on `stream` (a hipStream_t, NULL = the default stream) and returns without
+ * synchronising.  Outputs must not alias inputs.
  *
  * Supported: kernel 3x3; stride, dilation >= 1; pad >= 0; Cg in {8, 16, 32, 64};
  * dtype F32 or F16 (fp16 storage, fp32 positions, weights and accumulation, one
- * round-to-nearest at the store) for the forward; F32 for the backward.  One
- * image of x (H*W*G*Cg elements) must stay below 1 GiB.
+ * round-to-nearest at the store) for the forward; F32 for the backward.  Byte
+ * offsets inside one image are 32-bit: one image of x and of y, and the farthest
+ * clamped sampling position (about twice the image extent), must stay below 2 GiB;
+ * larger images are refused with DCNV4_ERR_UNSUPPORTED.
  *
  * Errors: every call validates its arguments on the host first and returns a
  * nonzero DCNV4_ERR_* without launching or writing anything; nothing throws or
