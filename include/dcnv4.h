@@ -97,6 +97,9 @@ long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
  *   "bwd_path"    1 = one kernel with global atomics for grad_x, 2 = two LDS-staged kernels (gathers
  *                 for grad_offset/grad_mask; LDS-private accumulation of grad_x), 0 = staged where
  *                 it applies (Cg 8 or 16 and a useful tile fits), else the first
+ *   "fwd_single"  LDS rectangle buffers of the staged gather kernels: 1 = always two (the next tile
+ *                 streams in during the current one), 2 = always one (bigger rectangle, refilled
+ *                 between tiles), 0 = one when that holds a whole image and two would need bands
  *   "gx_threads"  workgroup size of the staged grad_x kernel (256 or 512)
  *   "halo"        displacement in pixels that the staged window allows for (default 6);
  *                 samples beyond it are still exact, they take the global path

@@ -450,6 +450,7 @@ struct Options {
     int lds_kb = 0;        // LDS budget per workgroup of the tiled kernel, 0 = default
     int fwd_threads = 0;   // 256 or 512 for the tiled kernel, 0 = default
     int bwd_path = 0;      // 0 auto, 1 direct (global atomics), 2 LDS-tiled
+    int fwd_single = 0;    // rectangle buffers of the staged gather kernels: 0 auto, 1 always two, 2 always one
     int gx_threads = 0;    // workgroup size of the grad_x kernel (256 or 512), 0 = default
 } g_opt;
 
@@ -683,8 +684,29 @@ int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
     const int halo = g_opt.halo ? g_opt.halo : (gradx ? kDefaultHaloGradX : kDefaultHalo);
     int lds = (g_opt.lds_kb ? g_opt.lds_kb : kDefaultLdsKb) * 1024;
     if (lds > kMaxLdsBytes) lds = kMaxLdsBytes;
-    if (!choose_tile(q, threads, halo, lds, gradx ? 1 : 2, q.Cg * esize(q.dtype), gradx, &p))
-        return DCNV4_ERR_UNSUPPORTED;
+    const int pb = q.Cg * esize(q.dtype);
+    if (gradx) {
+        if (!choose_tile(q, threads, halo, lds, 1, pb, true, &p))
+            return DCNV4_ERR_UNSUPPORTED;
+        p.nbuf = 1;
+    } else {
+        // Two buffers overlap the copy of the next tile with the work on this one, but a tile switch
+        // costs a barrier and a drained pipeline; when an image only fits in bands that way and fits
+        // whole in one buffer, one buffer (no halo rows, no far samples, fewer switches) is better.
+        TGeo one;
+        memset(&one, 0, sizeof(one));
+        const bool ok2 = g_opt.fwd_single != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, &p);
+        const bool ok1 = g_opt.fwd_single != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, &one);
+        const bool whole1 = ok1 && one.R == q.Ho && one.tiles_q == 1;
+        if (!ok2 && !ok1)
+            return DCNV4_ERR_UNSUPPORTED;
+        if (!ok2 || (whole1 && p.tiles_per_img > 1) || g_opt.fwd_single == 2) {
+            p = one;
+            p.nbuf = 1;
+        } else {
+            p.nbuf = 2;
+        }
+    }
     const long long es = esize(q.dtype);
     const long long pgi = (long long)q.Ho * q.Wo * q.G;
     if (pgi >= 0x1000000)                    // offset/mask byte offsets inside one image stay in int32
@@ -731,7 +753,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
         return DCNV4_ERR_UNSUPPORTED;
     const int px_bytes = CG * (int)sizeof(T);
     const int tail = kGradX ? (p.xtile_bytes / px_bytes) * 4 + 16 : ((p.pitch + kTiledZeroPixelsExtra) * px_bytes + 15) & ~15;
-    const int lds = (kGradX ? 1 : 2) * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) + tail;
+    const int lds = p.nbuf * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) + tail;
     if (lds > kMaxLdsBytes)
         return DCNV4_ERR_UNSUPPORTED;
     auto kern = dcnv4_tiled_kernel<T, CG, THREADS, MODE>;
@@ -1013,6 +1035,10 @@ int dcnv4_set_option(const char *key, int value)
     }
     if (!strcmp(key, "gx_threads") && (value == 0 || value == 256 || value == 512)) {
         g_opt.gx_threads = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "fwd_single") && value >= 0 && value <= 2) {
+        g_opt.fwd_single = value;
         return DCNV4_OK;
     }
     if (!strcmp(key, "bwd_path") && value >= 0 && value <= 2) {
