@@ -607,18 +607,44 @@ constexpr int kMaxLdsBytes = 160 * 1024;
 // number of rows fits the LDS budget, otherwise split the columns too.  Returns false when
 // no tile with at least as many output rows/cols as the halo fits (the rectangle would be
 // mostly halo); the caller then uses the direct kernel.
+// Number of compute units of the current device (persistent kernels launch one workgroup each).
+int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
+            return 0;
+        cus = n;
+    }
+    return cus;
+}
+
 bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, TGeo *out)
 {
     const int es = esize(q.dtype);
     const int slices = (threads / 64) * 64 * 27 * es;
     const int need = halo > 4 ? halo : 4;
     const int waves = threads / 64;
-    for (int kq = 1; kq <= q.Wo; ++kq) {
+    int cus = device_cus();
+    if (cus <= 0) cus = 256;                 // no device in this process (host-only checks): assume a full MI355X
+    // Cost of a candidate (column splits kq, band height R), in units of one round (= every wave
+    // of a workgroup doing one batch of 64 output pixels): a tile of B batches takes ceil(B / waves)
+    // rounds plus about four for the switch (barrier, drained pipeline; measured), and a workgroup
+    // works through ceil(tiles / CUs) tiles -- so few, huge tiles that leave CUs idle lose against
+    // more, smaller ones.
+    double best_cost = 1e30;
+    bool found = false;
+    int splits_tried = 0;
+    for (int kq = 1; kq <= q.Wo && splits_tried < 12; ++kq) {
         const int Q = (q.Wo + kq - 1) / kq;
+        if (kq > 1 && Q == (q.Wo + kq - 2) / (kq - 1))
+            continue;                        // same tile width as the previous split count
         long long cols = (long long)(Q - 1) * q.sw + 2LL * q.dw + 2LL * halo + 2;
         if (cols > q.W + 4) cols = q.W + 4;
-        // the rectangle buffers (each a multiple of 1 KiB) share what the slices and the zero block leave
-        // after the slices: a block of zeros (pitch + 2 pixels), or one lock dword per rectangle pixel
+        // the rectangle buffers (each a multiple of 1 KiB) share what the slices leave, after
+        // a block of zeros (pitch + 2 pixels) or one lock dword per rectangle pixel
         const long long zero_bytes = locks ? 16 : ((cols + kTiledZeroPixelsExtra) * pb + 15) & ~15LL;
         const long long budget_px =
             ((((long long)lds_bytes - slices - zero_bytes) * pb / (pb + (locks ? 4 : 0)) / nbuf) & ~1023LL) / pb;
@@ -630,44 +656,33 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
         if (Rmax > q.Ho) Rmax = q.Ho;
         if (Rmax < 1 || (Rmax < need && Rmax < q.Ho) || (Q < need && Q < q.Wo))
             continue;
-        // Among the band heights that fit, take the one that wastes the fewest wave slots: a tile
-        // of B batches (64 output pixels each) keeps the workgroup busy for ceil(B / waves) rounds,
-        // and every tile also costs a barrier and a drained pipeline (measured: about four rounds).
+        ++splits_tried;
         const int tiles_q = (q.Wo + Q - 1) / Q;
-        const int Qlast = q.Wo - (tiles_q - 1) * Q;
-        long long best_R = Rmax;
-        double best_cost = 1e30;
         const long long Rlow = Rmax < need ? Rmax : need;
         for (long long R = Rmax; R >= Rlow; --R) {
             const long long bands = (q.Ho + R - 1) / R, Rlast = q.Ho - (bands - 1) * R;
-            double cost = 0;
-            for (int lastq = 0; lastq < 2; ++lastq) {
-                const long long nq = lastq ? 1 : tiles_q - 1;      // tiles of this width per band
-                if (nq == 0) continue;
-                (void)Qlast;                                        // narrower last column still walks R x Q slots
-                const long long b_full = (R * Q + 63) / 64, b_last = (Rlast * Q + 63) / 64;
-                cost += nq * ((bands - 1) * (double)((b_full + waves - 1) / waves) +
-                              (double)((b_last + waves - 1) / waves) + 4.0 * bands);
-            }
+            const long long b_full = (R * Q + 63) / 64, b_last = (Rlast * Q + 63) / 64;
+            const double rounds_img = tiles_q * ((bands - 1) * (double)((b_full + waves - 1) / waves) +
+                                                 (double)((b_last + waves - 1) / waves) + 4.0 * bands);
+            const long long tiles = (long long)q.N * q.G * bands * tiles_q;
+            const double per_tile = rounds_img / (double)(bands * tiles_q);
+            const double cost = (double)((tiles + cus - 1) / cus) * per_tile;
             if (cost < best_cost - 1e-9) {
                 best_cost = cost;
-                best_R = R;
+                found = true;
+                long long rows = (R - 1) * q.sh + 2LL * q.dh + 2LL * halo + 2;
+                if (rows > q.H + 4) rows = q.H + 4;
+                out->R = (int)R;
+                out->Q = Q;
+                out->halo = halo;
+                out->pitch = (int)cols;
+                out->tiles_q = tiles_q;
+                out->tiles_per_img = (int)(bands * tiles_q);
+                out->xtile_bytes = (int)((rows * cols * pb + 1023) & ~1023LL);
             }
         }
-        const long long R = best_R;
-        const int kr = (int)((q.Ho + R - 1) / R);
-        long long rows = (R - 1) * q.sh + 2LL * q.dh + 2LL * halo + 2;
-        if (rows > q.H + 4) rows = q.H + 4;
-        out->R = (int)R;
-        out->Q = Q;
-        out->halo = halo;
-        out->pitch = (int)cols;
-        out->tiles_q = tiles_q;
-        out->tiles_per_img = kr * tiles_q;
-        out->xtile_bytes = (int)((rows * cols * pb + 1023) & ~1023LL);
-        return true;
     }
-    return false;
+    return found;
 }
 
 // `gradx`: geometry for the grad_x kernel, whose single LDS rectangle holds Cg+1 fp32 per pixel.
@@ -765,14 +780,9 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
         granted = lds;
     }
     // persistent workgroups: one per compute unit (or fewer when there are fewer tiles)
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
-            return DCNV4_ERR_LAUNCH;
-        cus = n;
-    }
+    const int cus = device_cus();
+    if (cus <= 0)
+        return DCNV4_ERR_LAUNCH;
     unsigned grid;
     if (p.remap) {
         const int per = cus / kXcds < p.blocks_per_xcd ? cus / kXcds : p.blocks_per_xcd;

@@ -62,6 +62,14 @@ CONFIGS = {
 }
 CONFIGS["c5"] = CONFIGS["c2"].with_(name="c5")
 
+# The paper's own op-level benchmark shapes (Sec. 4.1, Tab. 2 and 3): 32 channels per group,
+# batch 64 for the standard shapes and batch 1 for the high-resolution ones.  Not benchmark
+# configs of this repository; kept so that a like-for-like line can be measured beside the
+# paper's A100 numbers.
+for _n, _h, _w, _c in ((64, 56, 56, 128), (64, 28, 28, 256), (64, 14, 14, 512), (64, 7, 7, 1024), (64, 14, 14, 768),
+                       (1, 200, 320, 128), (1, 100, 160, 256), (1, 50, 80, 512), (1, 25, 40, 1024), (1, 64, 64, 768)):
+    CONFIGS[f"paper_{_h}x{_w}x{_c}"] = Config(f"paper_{_h}x{_w}x{_c}", N=_n, H=_h, W=_w, C=_c, G=_c // 32)
+
 
 def make_inputs(cfg: Config, dtype: str = "f32", seed: int = 0, integer_fraction: float = 0.125):
     """Return dict(x, offset, mask, grad_y) of numpy arrays in `dtype` ('f32' or 'f16')."""
