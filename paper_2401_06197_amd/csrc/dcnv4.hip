@@ -450,6 +450,7 @@ struct Options {
     int lds_kb = 0;        // LDS budget per workgroup of the tiled kernel, 0 = default
     int fwd_threads = 0;   // 256 or 512 for the tiled kernel, 0 = default
     int bwd_path = 0;      // 0 auto, 1 direct (global atomics), 2 LDS-tiled
+    int wg_per_cu = 0;     // persistent workgroups per compute unit (1..4), 0 = default
     int fwd_single = 0;    // rectangle buffers of the staged gather kernels: 0 auto, 1 always two, 2 always one
     int gx_threads = 0;    // workgroup size of the grad_x kernel (256 or 512), 0 = default
 } g_opt;
@@ -783,12 +784,18 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
     const int cus = device_cus();
     if (cus <= 0)
         return DCNV4_ERR_LAUNCH;
+    // several persistent workgroups per compute unit when their LDS and registers fit: their tile
+    // switches (barrier, drained pipeline) then overlap with each other's work
+    int per_cu = g_opt.wg_per_cu ? g_opt.wg_per_cu : (MODE == kTiledFwd && THREADS == 256 && CG * sizeof(T) < 64 ? 2 : 1);
+    while (per_cu > 1 && (per_cu * lds > kMaxLdsBytes || per_cu * THREADS > 1024))
+        --per_cu;
+    const int slots = cus * per_cu;
     unsigned grid;
     if (p.remap) {
-        const int per = cus / kXcds < p.blocks_per_xcd ? cus / kXcds : p.blocks_per_xcd;
+        const int per = slots / kXcds < p.blocks_per_xcd ? slots / kXcds : p.blocks_per_xcd;
         grid = (unsigned)(per * kXcds);
     } else {
-        grid = (unsigned)(cus < p.nblocks ? cus : p.nblocks);
+        grid = (unsigned)(slots < p.nblocks ? slots : p.nblocks);
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds, s, (const T *)x, (const T *)off, (const T *)msk,
                        (const T *)gy, (T *)o1, (T *)o2, p);
@@ -812,10 +819,19 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
         // 64-byte pixels need more registers per lane than eight waves per workgroup leave
         if (g_opt.fwd_threads == 256 || (g_opt.fwd_threads == 0 && CG * sizeof(T) == 64))
             return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
-        if constexpr (CG * sizeof(T) < 64)
+        if constexpr (CG * sizeof(T) < 64) {
+            // Small whole-image tiles: two four-wave workgroups per compute unit, whose tile
+            // switches overlap with each other's work, beat one eight-wave workgroup.
+            if (g_opt.fwd_threads == 0) {
+                TGeo probe;
+                if (make_tgeo(q, 256, false, &probe) == DCNV4_OK && probe.tiles_per_img == 1 &&
+                    probe.R * probe.Q <= 16 * 64)
+                    return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
+            }
             return launch_fwd_tiled<T, CG, 512>(x, off, msk, y, q, s);
-        else
+        } else {
             return DCNV4_ERR_UNSUPPORTED;
+        }
     }
     return DCNV4_ERR_UNSUPPORTED;
 }
@@ -1049,6 +1065,10 @@ int dcnv4_set_option(const char *key, int value)
     }
     if (!strcmp(key, "fwd_single") && value >= 0 && value <= 2) {
         g_opt.fwd_single = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "wg_per_cu") && value >= 0 && value <= 4) {
+        g_opt.wg_per_cu = value;
         return DCNV4_OK;
     }
     if (!strcmp(key, "bwd_path") && value >= 0 && value <= 2) {
