@@ -756,7 +756,7 @@ int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
 // kernel-name record).
 template <typename T, int CG, int THREADS, int MODE>
 int launch_tiled(const void *x, const void *off, const void *msk, const void *gy, void *o1, void *o2,
-                 const Problem &q, hipStream_t s, int which)
+                 const Problem &q, hipStream_t s, int which, bool any_tile_size)
 {
     TGeo p;
     constexpr bool kGradX = MODE == kTiledGradX;
@@ -765,7 +765,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
         return rc;
     // a tile of one or two 64-pixel batches leaves most of the workgroup's waves idle and pays the
     // tile switch for almost no work: such images are left to the direct kernel unless forced
-    if (g_opt.fwd_path != 2 && p.R * p.Q < 128)
+    if (!any_tile_size && p.R * p.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
     const int px_bytes = CG * (int)sizeof(T);
     const int tail = kGradX ? (p.xtile_bytes / px_bytes) * 4 + 16 : ((p.pitch + kTiledZeroPixelsExtra) * px_bytes + 15) & ~15;
@@ -807,7 +807,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
 template <typename T, int CG, int THREADS>
 int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
-    return launch_tiled<T, CG, THREADS, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0);
+    return launch_tiled<T, CG, THREADS, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0, g_opt.fwd_path == 2);
 }
 
 // The tiled kernel keeps Cg fp32 accumulators and 4*Cg input values per lane, so it is built
@@ -922,13 +922,11 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     long long zb = (n16 + kThreads - 1) / kThreads;
     if (zb > 8192) zb = 8192;
     hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)gx, n16);
-    const int saved = g_opt.fwd_path;
-    g_opt.fwd_path = 2;                      // the size heuristic was applied above
-    rc = launch_tiled<float, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1);
+    // (the tile-size heuristic was applied above, to both geometries)
+    rc = launch_tiled<float, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
     if (rc == DCNV4_OK)
-        rc = gx512 ? launch_tiled<float, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1)
-                   : launch_tiled<float, CG, THREADS, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1);
-    g_opt.fwd_path = saved;
+        rc = gx512 ? launch_tiled<float, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
+                   : launch_tiled<float, CG, THREADS, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true);
     return rc;
 }
 

@@ -278,3 +278,42 @@ def test_gpu_call_with_bad_arguments_returns_error_and_writes_nothing():
         dcn.dcnv4_backward(h["x"], h["offset"], h["mask"], h["grad_y"])       # fp16 backward is not offered
     torch.cuda.synchronize()
     assert torch.all(y == 5.0)
+
+
+def test_forward_and_backward_replay_correctly_from_a_hip_graph():
+    """The library launches kernels only (grad_x is cleared by a kernel, not a memset node), so its
+    calls can be captured; every replay, with new input values in the same buffers and eager work
+    in between, must match the eager result."""
+    cfg = Config("graph", N=2, H=24, W=20, C=64, G=4)
+    h = to_gpu(make_inputs(cfg, "f16", seed=20), "f16")
+    f = to_gpu(make_inputs(cfg, "f32", seed=21), "f32")
+    y = torch.empty((cfg.N, cfg.H, cfg.W, cfg.C), dtype=torch.float16, device="cuda")
+    grads = (torch.empty_like(f["x"]), torch.empty_like(f["offset"]), torch.empty_like(f["mask"]))
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):                       # first calls outside the capture (one-time attribute set-up)
+        dcn.dcnv4_forward(h["x"], h["offset"], h["mask"], out=y, stream=s)
+        dcn.dcnv4_backward(f["x"], f["offset"], f["mask"], f["grad_y"], out=grads, stream=s)
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        dcn.dcnv4_forward(h["x"], h["offset"], h["mask"], out=y, stream=s)
+        dcn.dcnv4_backward(f["x"], f["offset"], f["mask"], f["grad_y"], out=grads, stream=s)
+    for rep in range(3):
+        nh = make_inputs(cfg, "f16", seed=30 + rep)
+        nf = make_inputs(cfg, "f32", seed=40 + rep)
+        for k in ("x", "offset", "mask"):
+            h[k].copy_(torch.from_numpy(nh[k]))
+        for k in ("x", "offset", "mask", "grad_y"):
+            f[k].copy_(torch.from_numpy(nf[k]))
+        y.fill_(3.0)
+        for t in grads:
+            t.fill_(3.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        close(f"graph{rep}/y", y.cpu().numpy(), oracle.forward(nh["x"], nh["offset"], nh["mask"]), TOL["f16"])
+        rgx, rgo, rgm = oracle.backward(nf["x"], nf["offset"], nf["mask"], nf["grad_y"])
+        close(f"graph{rep}/grad_x", grads[0].cpu().numpy(), rgx, TOL["f32"])
+        close(f"graph{rep}/grad_offset", grads[1].cpu().numpy(), rgo, TOL["f32"])
+        close(f"graph{rep}/grad_mask", grads[2].cpu().numpy(), rgm, TOL["f32"])
