@@ -622,7 +622,8 @@ int device_cus()
     return cus;
 }
 
-bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, TGeo *out)
+bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, TGeo *out,
+                 double *cost_out = nullptr)
 {
     const int es = esize(q.dtype);
     const int slices = (threads / 64) * 64 * 27 * es;
@@ -632,7 +633,8 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
     if (cus <= 0) cus = 256;                 // no device in this process (host-only checks): assume a full MI355X
     // Cost of a candidate (column splits kq, band height R), in units of one round (= every wave
     // of a workgroup doing one batch of 64 output pixels): a tile of B batches takes ceil(B / waves)
-    // rounds plus about four for the switch (barrier, drained pipeline; measured), and a workgroup
+    // rounds plus about four for the switch (barrier, drained pipeline; measured; six with a single
+    // buffer, whose refill is not hidden), and a workgroup
     // works through ceil(tiles / CUs) tiles -- so few, huge tiles that leave CUs idle lose against
     // more, smaller ones.
     double best_cost = 1e30;
@@ -664,7 +666,7 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
             const long long bands = (q.Ho + R - 1) / R, Rlast = q.Ho - (bands - 1) * R;
             const long long b_full = (R * Q + 63) / 64, b_last = (Rlast * Q + 63) / 64;
             const double rounds_img = tiles_q * ((bands - 1) * (double)((b_full + waves - 1) / waves) +
-                                                 (double)((b_last + waves - 1) / waves) + 4.0 * bands);
+                                                 (double)((b_last + waves - 1) / waves) + (nbuf == 1 && !locks ? 6.0 : 4.0) * bands);
             const long long tiles = (long long)q.N * q.G * bands * tiles_q;
             const double per_tile = rounds_img / (double)(bands * tiles_q);
             const double cost = (double)((tiles + cus - 1) / cus) * per_tile;
@@ -683,6 +685,8 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
             }
         }
     }
+    if (cost_out)
+        *cost_out = best_cost;
     return found;
 }
 
@@ -706,17 +710,17 @@ int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
             return DCNV4_ERR_UNSUPPORTED;
         p.nbuf = 1;
     } else {
-        // Two buffers overlap the copy of the next tile with the work on this one, but a tile switch
-        // costs a barrier and a drained pipeline; when an image only fits in bands that way and fits
-        // whole in one buffer, one buffer (no halo rows, no far samples, fewer switches) is better.
+        // Two buffers overlap the copy of the next tile with the work on this one; one buffer holds a
+        // rectangle twice as big (taller bands, fewer tile switches, less halo).  Take the cheaper one
+        // by the chooser's own estimate.
         TGeo one;
         memset(&one, 0, sizeof(one));
-        const bool ok2 = g_opt.fwd_single != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, &p);
-        const bool ok1 = g_opt.fwd_single != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, &one);
-        const bool whole1 = ok1 && one.R == q.Ho && one.tiles_q == 1;
+        double cost2 = 0, cost1 = 0;
+        const bool ok2 = g_opt.fwd_single != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, &p, &cost2);
+        const bool ok1 = g_opt.fwd_single != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, &one, &cost1);
         if (!ok2 && !ok1)
             return DCNV4_ERR_UNSUPPORTED;
-        if (!ok2 || (whole1 && p.tiles_per_img > 1) || g_opt.fwd_single == 2) {
+        if (!ok2 || (ok1 && cost1 < cost2)) {
             p = one;
             p.nbuf = 1;
         } else {
