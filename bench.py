@@ -3,7 +3,7 @@
 (N=64, 56x56, C=128, G=8, 3x3, stride 1, pad 1), synthetic seeded inputs.
 
 A step of the headline leg is one fp16 forward pass (the leg the 60 %-of-HBM-peak bar is
-quoted on); the same run also times the fp32 forward and the fp32 backward (grad_x,
+quoted on); the same run also times the fp32 forward and the fp32 and fp16 backward (grad_x,
 grad_offset, grad_mask) at the same shape and reports them under "legs".  Every leg rotates
 over several buffer sets whose total size exceeds the 256 MB memory-side cache, so a launch
 does not find its inputs in cache ("cold"); the back-to-back rate on one buffer set is
@@ -28,7 +28,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets rotated per leg")
-    ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32")
+    ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16")
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)

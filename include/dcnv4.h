@@ -27,7 +27,7 @@
  *
  * Supported: kernel 3x3; stride, dilation >= 1; pad >= 0; Cg in {8, 16, 32, 64};
  * dtype F32 or F16 (fp16 storage, fp32 positions, weights and accumulation, one
- * round-to-nearest at the store) for the forward; F32 for the backward.  Byte
+ * round-to-nearest at the store); the fp16 backward exists for Cg 8 and 16.  Byte
  * offsets inside one image are 32-bit: one image of x and of y, and the farthest
  * clamped sampling position (about twice the image extent), must stay below 2 GiB;
  * larger images are refused with DCNV4_ERR_UNSUPPORTED.
@@ -72,8 +72,10 @@ int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y,
  *   grad_mask_k  = sum_c gy[c] * S_k[c]
  *   grad_offset  = offset_scale * m_k * sum_c gy[c] * dS_k[c]/d(wx, hy)   (right-hand derivative
  *                  at whole-number coordinates)
- *   grad_x      += m_k * corner weight * gy[c]   at the in-image neighbours (fp32 atomics)
- * Overwrites all three outputs; grad_x is zero-filled on `stream` first. */
+ *   grad_x      += m_k * corner weight * gy[c]   at the in-image neighbours
+ * Overwrites all three outputs; grad_x is zero-filled on `stream` first.  Sums are fp32; in F16
+ * grad_offset/grad_mask are rounded once, grad_x receives its per-tile fp32 sums through packed
+ * fp16 atomics (a pixel is touched by the few tiles that reach it). */
 int dcnv4_backward(const void *x, const void *offset, const void *mask, const void *grad_y,
                    void *grad_x, void *grad_offset, void *grad_mask,
                    int N, int H, int W, int G, int Cg,

@@ -28,6 +28,7 @@ constexpr int kOutside = (int)0x80000000u;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 // n / d for 0 <= n < 2^31 as mulhi + add + shift (d >= 1), constants made on the host.
@@ -706,7 +707,7 @@ int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
     if (lds > kMaxLdsBytes) lds = kMaxLdsBytes;
     const int pb = q.Cg * esize(q.dtype);
     if (gradx) {
-        if (!choose_tile(q, threads, halo, lds, 1, pb, true, &p))
+        if (!choose_tile(q, threads, halo, lds, 1, q.Cg * 4, true, &p))
             return DCNV4_ERR_UNSUPPORTED;
         p.nbuf = 1;
     } else {
@@ -771,7 +772,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
     // tile switch for almost no work: such images are left to the direct kernel unless forced
     if (!any_tile_size && p.R * p.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
-    const int px_bytes = CG * (int)sizeof(T);
+    const int px_bytes = kGradX ? CG * 4 : CG * (int)sizeof(T);
     const int tail = kGradX ? (p.xtile_bytes / px_bytes) * 4 + 16 : ((p.pitch + kTiledZeroPixelsExtra) * px_bytes + 15) & ~15;
     const int lds = p.nbuf * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) + tail;
     if (lds > kMaxLdsBytes)
@@ -905,11 +906,11 @@ int dispatch_bwd_cpt(int cpt, const void *x, const void *off, const void *msk, c
 // Backward through the LDS-staged kernels: zero-fill of grad_x, then the grad_offset/grad_mask
 // pass (gathers, like the forward) and the grad_x pass (LDS-private accumulation, one flush per
 // tile).  Both are validated before anything is launched, so an unsupported shape writes nothing.
-template <int CG>
+template <typename T, int CG>
 int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void *gy, void *gx, void *go, void *gm,
                      const Problem &q, hipStream_t s)
 {
-    constexpr int THREADS = 256;             // 64-byte pixels: four waves per workgroup
+    constexpr int THREADS = 256;             // the gather pass keeps 4*Cg inputs and gy per lane: four waves
     TGeo probe;
     int rc = make_tgeo(q, THREADS, false, &probe);
     if (rc)
@@ -927,10 +928,10 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     if (zb > 8192) zb = 8192;
     hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)gx, n16);
     // (the tile-size heuristic was applied above, to both geometries)
-    rc = launch_tiled<float, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
+    rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
     if (rc == DCNV4_OK)
-        rc = gx512 ? launch_tiled<float, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
-                   : launch_tiled<float, CG, THREADS, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true);
+        rc = gx512 ? launch_tiled<T, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
+                   : launch_tiled<T, CG, THREADS, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true);
     return rc;
 }
 
@@ -1005,15 +1006,23 @@ int dcnv4_backward(const void *x, const void *offset, const void *mask, const vo
     rc = validate(q, kernel_h, kernel_w, ptrs, 7);
     if (rc)
         return rc;
-    if (dtype != DCNV4_F32)
-        return DCNV4_ERR_UNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
+    if (dtype == DCNV4_F16) {
+        // fp16 storage, fp32 arithmetic; only the LDS-staged kernels exist for it (Cg 8 or 16)
+        if (g_opt.bwd_path == 1)
+            return DCNV4_ERR_UNSUPPORTED;
+        if (Cg == 8)
+            return launch_bwd_tiled<_Float16, 8>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+        if (Cg == 16)
+            return launch_bwd_tiled<_Float16, 16>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+        return DCNV4_ERR_UNSUPPORTED;
+    }
     if (g_opt.bwd_path != 1) {
         rc = DCNV4_ERR_UNSUPPORTED;
         if (Cg == 8)
-            rc = launch_bwd_tiled<8>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            rc = launch_bwd_tiled<float, 8>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         else if (Cg == 16)
-            rc = launch_bwd_tiled<16>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            rc = launch_bwd_tiled<float, 16>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.bwd_path == 2)
             return rc;
     }

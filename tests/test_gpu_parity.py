@@ -47,17 +47,17 @@ def check_forward(cfg, dtype, seed=0, inputs=None):
     return close(f"{cfg.name}/{dtype}/y", y.cpu().numpy(), ref, TOL[dtype])
 
 
-def check_backward(cfg, seed=0, inputs=None):
-    t = inputs if inputs is not None else make_inputs(cfg, "f32", seed=seed)
-    d = to_gpu(t, "f32")
+def check_backward(cfg, seed=0, inputs=None, dtype="f32"):
+    t = inputs if inputs is not None else make_inputs(cfg, dtype, seed=seed)
+    d = to_gpu(t, dtype)
     # poison the outputs: the call must overwrite all three
     out = (torch.full_like(d["x"], 7.0), torch.full_like(d["offset"], 7.0), torch.full_like(d["mask"], 7.0))
     gx, go, gm = dcn.dcnv4_backward(d["x"], d["offset"], d["mask"], d["grad_y"], out=out, **geo_kw(cfg))
     torch.cuda.synchronize()
     rgx, rgo, rgm = oracle.backward(t["x"], t["offset"], t["mask"], t["grad_y"], **geo_kw(cfg))
-    close(f"{cfg.name}/grad_mask", gm.cpu().numpy(), rgm, TOL["f32"])
-    close(f"{cfg.name}/grad_offset", go.cpu().numpy(), rgo, TOL["f32"])
-    close(f"{cfg.name}/grad_x", gx.cpu().numpy(), rgx, TOL["f32"])
+    close(f"{cfg.name}/{dtype}/grad_mask", gm.cpu().numpy(), rgm, TOL[dtype])
+    close(f"{cfg.name}/{dtype}/grad_offset", go.cpu().numpy(), rgo, TOL[dtype])
+    close(f"{cfg.name}/{dtype}/grad_x", gx.cpu().numpy(), rgx, TOL[dtype])
 
 
 # ------------------------------------------------------------------ the five benchmark configs
@@ -83,6 +83,30 @@ def test_c4_high_resolution_forward_fp16():
 def test_c5_training_step_full_size_fp32():
     check_forward(CONFIGS["c5"], "f32")
     check_backward(CONFIGS["c5"])
+
+
+def test_c5_shape_backward_fp16():
+    """fp16 storage with fp32 arithmetic; grad_x collects its fp32 tile sums with packed fp16 atomics."""
+    check_backward(CONFIGS["c5"], dtype="f16")
+    check_backward(CONFIGS["c1"], dtype="f16")
+
+
+FP16_BWD = [Config("hb1", N=3, H=20, W=23, C=64, G=4), Config("hb8", N=2, H=11, W=10, C=16, G=2),
+            Config("hbs2", N=2, H=21, W=17, C=32, G=2, stride=2, pad=2, dilation=2, sigma=3.0),
+            Config("hbwide", N=1, H=9, W=70, C=48, G=3, sigma=5.0), Config("hbrow", N=1, H=1, W=37, C=32, G=2)]
+
+
+@pytest.mark.parametrize("cfg", FP16_BWD, ids=[c.name for c in FP16_BWD])
+@pytest.mark.parametrize("opts", [{}, {"halo": 1}, {"gx_threads": 256, "fwd_single": 1}], ids=["default", "halo1", "gx256"])
+def test_fp16_backward_geometries(cfg, opts):
+    try:
+        for k, v in opts.items():
+            dcn.dcnv4_set_option(k, v)
+        dcn.dcnv4_set_option("bwd_path", 2)
+        check_backward(cfg, seed=12, dtype="f16")
+    finally:
+        for k in list(opts) + ["bwd_path"]:
+            dcn.dcnv4_set_option(k, 0)
 
 
 # ------------------------------------------------------------------ geometry / tiling coverage
@@ -274,8 +298,8 @@ def test_gpu_call_with_bad_arguments_returns_error_and_writes_nothing():
                           kernel=5, out=y[:, :6, :6].contiguous())
     assert e.value.status == 3
     with pytest.raises(dcn.Dcnv4Error):
-        h = {k: v.half() for k, v in d.items()}
-        dcn.dcnv4_backward(h["x"], h["offset"], h["mask"], h["grad_y"])       # fp16 backward is not offered
+        wide = to_gpu(make_inputs(Config("wide", N=1, H=8, W=8, C=64, G=2), "f16", seed=11), "f16")
+        dcn.dcnv4_backward(wide["x"], wide["offset"], wide["mask"], wide["grad_y"])   # fp16 backward: Cg 8 or 16 only
     torch.cuda.synchronize()
     assert torch.all(y == 5.0)
 
