@@ -102,13 +102,13 @@ long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
  *   "fwd_single"  LDS rectangle buffers of the staged gather kernels: 1 = always two (the next tile
  *                 streams in during the current one), 2 = always one (bigger rectangle, refilled
  *                 between tiles), 0 = one when that holds a whole image and two would need bands
- *   "wg_per_cu"   persistent workgroups per compute unit of the staged kernels (1..4, as far as LDS
- *                 allows); default 2 for the four-wave forward, else 1
+ *   "wg_per_cu"   persistent workgroups per compute unit of the staged kernels (1..16, as far as LDS
+ *                 allows); default 8 / 2 / 1 for the one- / four- / eight-wave forward, else 1
  *   "gx_threads"  workgroup size of the staged grad_x kernel (256 or 512)
  *   "halo"        displacement in pixels that the staged window allows for (default 6);
  *                 samples beyond it are still exact, they take the global path
  *   "lds_kb"      LDS budget per workgroup of the staged kernel (8..160)
- *   "fwd_threads" workgroup size of the staged forward (256 or 512; default by tile size)
+ *   "fwd_threads" workgroup size of the staged forward (64, 256 or 512; default by tile size)
  *   "fwd_cpt"     channels per thread in the direct forward kernel (8 or 16)
  *   "bwd_cpt"     channels per thread in the backward kernel (4, 8 or 16)
  *   "xcd_remap"   1 = hand consecutive tiles to one XCD (default), 0 = plain block order

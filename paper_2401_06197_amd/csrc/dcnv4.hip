@@ -791,8 +791,8 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
         return DCNV4_ERR_LAUNCH;
     // several persistent workgroups per compute unit when their LDS and registers fit: their tile
     // switches (barrier, drained pipeline) then overlap with each other's work
-    int per_cu = g_opt.wg_per_cu ? g_opt.wg_per_cu : (MODE == kTiledFwd && THREADS == 256 && CG * sizeof(T) < 64 ? 2 : 1);
-    while (per_cu > 1 && (per_cu * lds > kMaxLdsBytes || per_cu * THREADS > 1024))
+    int per_cu = g_opt.wg_per_cu ? g_opt.wg_per_cu : (MODE != kTiledFwd || CG * sizeof(T) >= 64 ? 1 : THREADS == 256 ? 2 : THREADS == 64 ? 8 : 1);
+    while (per_cu > 1 && (per_cu * lds > kMaxLdsBytes || per_cu * THREADS > 2048))
         --per_cu;
     const int slots = cus * per_cu;
     unsigned grid;
@@ -827,6 +827,15 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
         if constexpr (CG * sizeof(T) < 64) {
             // Small whole-image tiles: two four-wave workgroups per compute unit, whose tile
             // switches overlap with each other's work, beat one eight-wave workgroup.
+            if (g_opt.fwd_threads == 64)
+                return launch_fwd_tiled<T, CG, 64>(x, off, msk, y, q, s);
+            if (g_opt.fwd_threads == 0 && g_opt.fwd_path != 1) {
+                // An image of one or two batches: one-wave workgroups, eight to a compute unit, so that
+                // no wave idles while another works (beats the direct kernel on 7x7 maps).
+                TGeo tiny;
+                if (make_tgeo(q, 64, false, &tiny) == DCNV4_OK && tiny.tiles_per_img == 1 && tiny.R * tiny.Q <= 128)
+                    return launch_tiled<T, CG, 64, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0, true);
+            }
             if (g_opt.fwd_threads == 0) {
                 TGeo probe;
                 if (make_tgeo(q, 256, false, &probe) == DCNV4_OK && probe.tiles_per_img == 1 &&
@@ -1078,7 +1087,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.fwd_single = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "wg_per_cu") && value >= 0 && value <= 4) {
+    if (!strcmp(key, "wg_per_cu") && value >= 0 && value <= 16) {
         g_opt.wg_per_cu = value;
         return DCNV4_OK;
     }
@@ -1094,7 +1103,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.lds_kb = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 256 || value == 512)) {
+    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 64 || value == 256 || value == 512)) {
         g_opt.fwd_threads = value;
         return DCNV4_OK;
     }

@@ -146,6 +146,7 @@ FWD_VARIANTS = [
     {"fwd_path": 2, "halo": 1}, {"fwd_path": 2, "halo": 2, "lds_kb": 48}, {"fwd_path": 2, "halo": 12, "lds_kb": 160},
     {"fwd_path": 2, "halo": 3, "lds_kb": 40, "fwd_threads": 256},
     {"fwd_path": 2, "fwd_threads": 256, "wg_per_cu": 3, "lds_kb": 50}, {"fwd_path": 2, "fwd_threads": 512, "wg_per_cu": 1},
+    {"fwd_path": 2, "fwd_threads": 64}, {"fwd_path": 2, "fwd_threads": 64, "wg_per_cu": 16, "lds_kb": 24, "halo": 2},
     {"fwd_path": 2, "fwd_single": 2}, {"fwd_path": 2, "fwd_single": 1}, {"fwd_path": 2, "fwd_single": 2, "lds_kb": 64, "halo": 2},
 ]
 
