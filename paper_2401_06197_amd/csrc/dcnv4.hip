@@ -924,13 +924,15 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     int rc = make_tgeo(q, THREADS, false, &probe);
     if (rc)
         return rc;
-    if (g_opt.bwd_path != 2 && probe.R * probe.Q < 128)
+    // (for fp16 there is no other backward, so the tile-size heuristic does not apply)
+    const bool any_size = g_opt.bwd_path == 2 || sizeof(T) == 2;
+    if (!any_size && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
     const bool gx512 = g_opt.gx_threads != 256;      // eight waves hide the lock round trips better than four
     rc = make_tgeo(q, gx512 ? 512 : THREADS, true, &probe);
     if (rc)
         return rc;
-    if (g_opt.bwd_path != 2 && probe.R * probe.Q < 128)
+    if (!any_size && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
     const long long n16 = (long long)q.N * probe.x_img_bytes / 16;
     long long zb = (n16 + kThreads - 1) / kThreads;

@@ -342,3 +342,48 @@ def test_forward_and_backward_replay_correctly_from_a_hip_graph():
         close(f"graph{rep}/grad_x", grads[0].cpu().numpy(), rgx, TOL["f32"])
         close(f"graph{rep}/grad_offset", grads[1].cpu().numpy(), rgo, TOL["f32"])
         close(f"graph{rep}/grad_mask", grads[2].cpu().numpy(), rgm, TOL["f32"])
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        k = dict(N=int(rng.integers(1, 4)), H=int(rng.integers(1, 41)), W=int(rng.integers(1, 41)),
+                 G=int(rng.integers(1, 6)), stride=int(rng.integers(1, 4)), pad=int(rng.integers(0, 4)),
+                 dilation=int(rng.integers(1, 4)), sigma=float(rng.choice([0.5, 1.0, 2.0, 4.0, 7.0])),
+                 offset_scale=float(rng.choice([1.0, 1.0, 0.5, 2.0])))
+        cg = int(rng.choice([8, 16, 16, 32]))
+        span = k["dilation"] * 2 + 1
+        if k["H"] + 2 * k["pad"] < span or k["W"] + 2 * k["pad"] < span:
+            continue
+        opts = {}
+        if rng.random() < 0.6:
+            opts["halo"] = int(rng.integers(1, 9))
+        if rng.random() < 0.6:
+            opts["lds_kb"] = int(rng.choice([40, 64, 100, 160]))
+        if rng.random() < 0.3:
+            opts["fwd_single"] = int(rng.integers(1, 3))
+        if rng.random() < 0.3:
+            opts["fwd_threads"] = int(rng.choice([64, 256, 512]))
+        cases.append((Config(f"rnd{len(cases)}", C=k["G"] * cg, **k), opts))
+    return cases
+
+
+@pytest.mark.parametrize("cfg,opts", _random_cases(40, 2024), ids=lambda v: v.name if isinstance(v, Config) else "o")
+def test_random_geometries_and_tilings(cfg, opts):
+    """Seeded random shapes, strides, pads, dilations, offset spreads and tiling options: whichever
+    kernel the dispatch picks, forward and backward must match the oracle."""
+    try:
+        for k, v in opts.items():
+            dcn.dcnv4_set_option(k, v)
+        check_forward(cfg, "f16", seed=50)
+        check_forward(cfg, "f32", seed=51)
+        check_backward(cfg, seed=52)
+        if cfg.Cg <= 16:
+            try:
+                check_backward(cfg, seed=53, dtype="f16")
+            except dcn.Dcnv4Error as e:      # the fp16 backward has only the staged kernels: a small LDS budget can rule them out
+                assert e.status == 3 and "lds_kb" in opts
+    finally:
+        for k in opts:
+            dcn.dcnv4_set_option(k, 0)
