@@ -121,6 +121,24 @@ template <int CPT> struct Vec<float, CPT> {
     }
     __device__ __forceinline__ float get(int c) const { return v[c / 4][c % 4]; }
 };
+template <> struct Vec<float, 2> {              // narrow runs: the backward's lane-per-channel layouts
+    float v[2];
+    __device__ __forceinline__ void load(rsrc_t r, int off)
+    {
+        // two dword loads (the 64-bit raw buffer load builtin of this compiler fetches one dword only)
+        v[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
+        v[1] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, off + 4, 0, 0));
+    }
+    __device__ __forceinline__ float get(int c) const { return v[c]; }
+};
+template <> struct Vec<float, 1> {
+    float v;
+    __device__ __forceinline__ void load(rsrc_t r, int off)
+    {
+        v = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
+    }
+    __device__ __forceinline__ float get(int) const { return v; }
+};
 
 template <int CPT>
 __device__ __forceinline__ void store_run(rsrc_t r, int off, const float (&a)[CPT], _Float16 *)
@@ -312,9 +330,13 @@ __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict
 #include "dcnv4_tiled.inc"
 
 // ------------------------------------------------------------------------------------------
-// Backward (chain rule on Eq. 1), fp32.  Same thread organisation as the forward.  The
-// per-channel products are reduced inside the thread; when a group is split over TPG lanes
-// the partial sums are combined with DPP lane exchanges inside one 16-lane row.
+// Backward (chain rule on Eq. 1), fp32, in one pass with grad_x added straight to memory; used
+// where the LDS-staged kernels do not apply (groups wider than 16 channels, tiny images).  A group
+// is spread over TPG lanes of CPT channels each -- by default one channel per lane, so that a
+// wave's atomic instruction covers a few whole cache lines; the L2 atomic units then sustain about
+// eight times the rate they reach when every lane adds to a line of its own.  The lanes' partial
+// sums for grad_offset/grad_mask are combined with DPP exchanges inside a 16-lane row (plus one
+// swizzle for 32 lanes).
 // grad_offset / grad_mask leave through the same LDS tile the inputs came in by.
 // ------------------------------------------------------------------------------------------
 template <int CTRL>
@@ -331,6 +353,8 @@ __device__ __forceinline__ float group_sum(float v)
     if (TPG >= 4) v = dpp_add<0x4E>(v);      // quad_perm [2,3,0,1]
     if (TPG >= 8) v = dpp_add<0x141>(v);     // row_half_mirror
     if (TPG >= 16) v = dpp_add<0x140>(v);    // row_mirror
+    if (TPG >= 32)                           // the other 16-lane row of the 32-lane half: swizzle, lane ^ 16
+        v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
     return v;
 }
 
@@ -553,7 +577,9 @@ int default_fwd_cpt(int dtype, int Cg)
     (void)dtype;
     return Cg == 8 ? 8 : 8;      // 16-byte (fp16) or 32-byte (fp32) runs per lane: neighbouring lanes share cache lines
 }
-int default_bwd_cpt(int Cg) { return Cg == 8 ? 8 : 8; }
+// One or two channels per lane: a wave's atomic instruction then covers a few whole cache lines
+// (16 lanes x 4 or 8 bytes per pixel) instead of 64 different ones, and the L2 atomic rate follows.
+int default_bwd_cpt(int Cg) { return Cg <= 32 ? 1 : Cg / 32; }
 
 int pick_fwd_cpt(int dtype, int Cg)
 {
@@ -566,7 +592,7 @@ int pick_bwd_cpt(int Cg)
 {
     int c = g_opt.bwd_cpt ? g_opt.bwd_cpt : default_bwd_cpt(Cg);
     if (c > Cg) c = Cg;
-    if (Cg / c > 16) c = Cg / 16;      // the lane reduction stays inside one 16-lane row
+    if (Cg / c > 32) c = Cg / 32;      // the lane reduction spans at most two 16-lane rows
     return c;
 }
 
@@ -909,6 +935,12 @@ int dispatch_bwd_cpt(int cpt, const void *x, const void *off, const void *msk, c
     if constexpr (CG <= 64) {
         if (cpt == 4) return launch_bwd<CG, 4>(x, off, msk, gy, gx, go, gm, q, s);
     }
+    if constexpr (CG <= 64) {
+        if (cpt == 2) return launch_bwd<CG, 2>(x, off, msk, gy, gx, go, gm, q, s);
+    }
+    if constexpr (CG <= 32) {
+        if (cpt == 1) return launch_bwd<CG, 1>(x, off, msk, gy, gx, go, gm, q, s);
+    }
     return DCNV4_ERR_UNSUPPORTED;
 }
 
@@ -1069,7 +1101,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.fwd_cpt = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "bwd_cpt") && (value == 0 || value == 4 || value == 8 || value == 16)) {
+    if (!strcmp(key, "bwd_cpt") && (value == 0 || value == 1 || value == 2 || value == 4 || value == 8 || value == 16)) {
         g_opt.bwd_cpt = value;
         return DCNV4_OK;
     }
