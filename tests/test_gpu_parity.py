@@ -388,3 +388,38 @@ def test_random_geometries_and_tilings(cfg, opts):
     finally:
         for k in opts:
             dcn.dcnv4_set_option(k, 0)
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_every_sample_on_the_same_pixels_contends_but_stays_exact(path):
+    """Worst case for the grad_x accumulation: every tap of every output pixel lands in the same 2x2
+    neighbourhood, so all lanes of all waves fight over four accumulators (lock path) or four cache
+    lines (atomic path)."""
+    cfg = Config("pile", N=1, H=12, W=10, C=32, G=2)
+    t = make_inputs(cfg, "f32", seed=60)
+    off = np.empty_like(t["offset"])
+    for oh in range(cfg.H):
+        for ow in range(cfg.W):
+            for j in range(3):
+                for i in range(3):
+                    k = j * 3 + i
+                    off[0, oh, ow, :, k, 1] = 3.5 - (oh - 1 + i)
+                    off[0, oh, ow, :, k, 0] = 2.25 - (ow - 1 + j)
+    t["offset"] = off
+    try:
+        dcn.dcnv4_set_option("bwd_path", path)
+        check_forward(cfg, "f32", inputs=t)
+        check_backward(cfg, inputs=t)
+        if path == 2:
+            h = {k: v.astype(np.float16) for k, v in t.items()}
+            check_forward(cfg, "f16", inputs=h)
+            d = to_gpu(h, "f16")
+            gx, go, gm = dcn.dcnv4_backward(d["x"], d["offset"], d["mask"], d["grad_y"])
+            rgx, rgo, rgm = oracle.backward(h["x"], h["offset"], h["mask"], h["grad_y"])
+            close("pile/f16/grad_mask", gm.cpu().numpy(), rgm, TOL["f16"])
+            close("pile/f16/grad_offset", go.cpu().numpy(), rgo, TOL["f16"])
+            # 1080 contributions per channel pile up in four pixels: the tile sums are fp32, only the
+            # final value is rounded to fp16
+            close("pile/f16/grad_x", gx.cpu().numpy(), rgx, TOL["f16"])
+    finally:
+        dcn.dcnv4_set_option("bwd_path", 0)
