@@ -951,7 +951,8 @@ template <typename T, int CG>
 int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void *gy, void *gx, void *go, void *gm,
                      const Problem &q, hipStream_t s)
 {
-    constexpr int THREADS = 256;             // the gather pass keeps 4*Cg inputs and gy per lane: four waves
+    // the gather pass keeps 4*Cg inputs and gy per lane: eight waves fit the register file in fp16, four in fp32
+    constexpr int THREADS = sizeof(T) == 2 ? 512 : 256;
     TGeo probe;
     int rc = make_tgeo(q, THREADS, false, &probe);
     if (rc)
@@ -961,7 +962,7 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     if (!any_size && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
     const bool gx512 = g_opt.gx_threads != 256;      // eight waves hide the lock round trips better than four
-    rc = make_tgeo(q, gx512 ? 512 : THREADS, true, &probe);
+    rc = make_tgeo(q, gx512 ? 512 : 256, true, &probe);
     if (rc)
         return rc;
     if (!any_size && probe.R * probe.Q < 128)
@@ -974,7 +975,7 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
     if (rc == DCNV4_OK)
         rc = gx512 ? launch_tiled<T, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
-                   : launch_tiled<T, CG, THREADS, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true);
+                   : launch_tiled<T, CG, 256, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true);
     return rc;
 }
 
