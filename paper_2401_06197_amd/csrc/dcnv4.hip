@@ -649,11 +649,12 @@ int device_cus()
     return cus;
 }
 
-bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, TGeo *out,
-                 double *cost_out = nullptr)
+bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, bool with_slices,
+                 TGeo *out, double *cost_out = nullptr)
 {
     const int es = esize(q.dtype);
-    const int slices = (threads / 64) * 64 * 27 * es;
+    // per-wave LDS slices for the 27 offset/mask values of 64 pixels (grad_offset/grad_mask pass only)
+    const int slices = with_slices ? (threads / 64) * 64 * 27 * es : 0;
     const int need = halo > 4 ? halo : 4;
     const int waves = threads / 64;
     int cus = device_cus();
@@ -717,9 +718,11 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
     return found;
 }
 
-// `gradx`: geometry for the grad_x kernel, whose single LDS rectangle holds Cg+1 fp32 per pixel.
-int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
+// `mode`: kTiledGradX has a single LDS rectangle of Cg fp32 per pixel plus one lock dword per pixel;
+// kTiledGradOM additionally keeps per-wave slices for the offset/mask values.
+int make_tgeo(const Problem &q, int threads, int mode, TGeo *out)
 {
+    const bool gradx = mode == kTiledGradX, with_slices = mode == kTiledGradOM;
     Geo base;
     int rc = make_geo(q, 1, &base);          // shares the 32-bit offset validation
     if (rc)
@@ -733,7 +736,7 @@ int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
     if (lds > kMaxLdsBytes) lds = kMaxLdsBytes;
     const int pb = q.Cg * esize(q.dtype);
     if (gradx) {
-        if (!choose_tile(q, threads, halo, lds, 1, q.Cg * 4, true, &p))
+        if (!choose_tile(q, threads, halo, lds, 1, q.Cg * 4, true, false, &p))
             return DCNV4_ERR_UNSUPPORTED;
         p.nbuf = 1;
     } else {
@@ -743,8 +746,8 @@ int make_tgeo(const Problem &q, int threads, bool gradx, TGeo *out)
         TGeo one;
         memset(&one, 0, sizeof(one));
         double cost2 = 0, cost1 = 0;
-        const bool ok2 = g_opt.fwd_single != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, &p, &cost2);
-        const bool ok1 = g_opt.fwd_single != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, &one, &cost1);
+        const bool ok2 = g_opt.fwd_single != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, with_slices, &p, &cost2);
+        const bool ok1 = g_opt.fwd_single != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, with_slices, &one, &cost1);
         if (!ok2 && !ok1)
             return DCNV4_ERR_UNSUPPORTED;
         if (!ok2 || (ok1 && cost1 < cost2)) {
@@ -791,7 +794,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
 {
     TGeo p;
     constexpr bool kGradX = MODE == kTiledGradX;
-    int rc = make_tgeo(q, THREADS, kGradX, &p);
+    int rc = make_tgeo(q, THREADS, MODE, &p);
     if (rc)
         return rc;
     // a tile of one or two 64-pixel batches leaves most of the workgroup's waves idle and pays the
@@ -800,7 +803,8 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
         return DCNV4_ERR_UNSUPPORTED;
     const int px_bytes = kGradX ? CG * 4 : CG * (int)sizeof(T);
     const int tail = kGradX ? (p.xtile_bytes / px_bytes) * 4 + 16 : ((p.pitch + kTiledZeroPixelsExtra) * px_bytes + 15) & ~15;
-    const int lds = p.nbuf * p.xtile_bytes + (THREADS / 64) * 64 * 27 * (int)sizeof(T) + tail;
+    const int slices = MODE == kTiledGradOM ? (THREADS / 64) * 64 * 27 * (int)sizeof(T) : 0;
+    const int lds = p.nbuf * p.xtile_bytes + slices + tail;
     if (lds > kMaxLdsBytes)
         return DCNV4_ERR_UNSUPPORTED;
     auto kern = dcnv4_tiled_kernel<T, CG, THREADS, MODE>;
@@ -859,12 +863,12 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
                 // An image of one or two batches: one-wave workgroups, eight to a compute unit, so that
                 // no wave idles while another works (beats the direct kernel on 7x7 maps).
                 TGeo tiny;
-                if (make_tgeo(q, 64, false, &tiny) == DCNV4_OK && tiny.tiles_per_img == 1 && tiny.R * tiny.Q <= 128)
+                if (make_tgeo(q, 64, kTiledFwd, &tiny) == DCNV4_OK && tiny.tiles_per_img == 1 && tiny.R * tiny.Q <= 128)
                     return launch_tiled<T, CG, 64, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0, true);
             }
             if (g_opt.fwd_threads == 0) {
                 TGeo probe;
-                if (make_tgeo(q, 256, false, &probe) == DCNV4_OK && probe.tiles_per_img == 1 &&
+                if (make_tgeo(q, 256, kTiledFwd, &probe) == DCNV4_OK && probe.tiles_per_img == 1 &&
                     probe.R * probe.Q <= 16 * 64)
                     return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
             }
@@ -954,7 +958,7 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     // the gather pass keeps 4*Cg inputs and gy per lane: eight waves fit the register file in fp16, four in fp32
     constexpr int THREADS = sizeof(T) == 2 ? 512 : 256;
     TGeo probe;
-    int rc = make_tgeo(q, THREADS, false, &probe);
+    int rc = make_tgeo(q, THREADS, kTiledGradOM, &probe);
     if (rc)
         return rc;
     // (for fp16 there is no other backward, so the tile-size heuristic does not apply)
@@ -962,7 +966,7 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     if (!any_size && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
     const bool gx512 = g_opt.gx_threads != 256;      // eight waves hide the lock round trips better than four
-    rc = make_tgeo(q, gx512 ? 512 : 256, true, &probe);
+    rc = make_tgeo(q, gx512 ? 512 : 256, kTiledGradX, &probe);
     if (rc)
         return rc;
     if (!any_size && probe.R * probe.Q < 128)
