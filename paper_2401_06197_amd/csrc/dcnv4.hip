@@ -851,8 +851,13 @@ template <typename T, int CG>
 int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
     if constexpr (CG * sizeof(T) <= 64 && CG * sizeof(T) >= 16) {
-        // 64-byte pixels need more registers per lane than eight waves per workgroup leave
-        if (g_opt.fwd_threads == 256 || (g_opt.fwd_threads == 0 && CG * sizeof(T) == 64))
+        if constexpr (CG * sizeof(T) == 64) {
+            // 64-byte pixels: eight waves still fit the register file (no LDS slices, no exchange registers)
+            if (g_opt.fwd_threads == 256)
+                return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
+            return launch_fwd_tiled<T, CG, 512>(x, off, msk, y, q, s);
+        }
+        if (g_opt.fwd_threads == 256)
             return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
         if constexpr (CG * sizeof(T) < 64) {
             // Small whole-image tiles: two four-wave workgroups per compute unit, whose tile
