@@ -475,6 +475,7 @@ struct Options {
     int lds_kb = 0;        // LDS budget per workgroup of the tiled kernel, 0 = default
     int fwd_threads = 0;   // 256 or 512 for the tiled kernel, 0 = default
     int bwd_path = 0;      // 0 auto, 1 direct (global atomics), 2 LDS-tiled
+    int batch_order = 0;   // 0 default (blocked in grad_x, interleaved elsewhere), 1 interleaved, 2 blocked
     int wg_per_cu = 0;     // persistent workgroups per compute unit (1..4), 0 = default
     int fwd_single = 0;    // rectangle buffers of the staged gather kernels: 0 auto, 1 always two, 2 always one
     int gx_threads = 0;    // workgroup size of the grad_x kernel (256 or 512), 0 = default
@@ -771,6 +772,7 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out)
     p.nblocks = (int)nblocks;
     p.blocks_per_xcd = (int)((nblocks + kXcds - 1) / kXcds);
     p.remap = g_opt.xcd_remap;
+    p.blocked = g_opt.batch_order ? g_opt.batch_order == 2 : gradx;
     p.div_g = make_div((unsigned)q.G);
     p.div_tpi = make_div((unsigned)p.tiles_per_img);
     p.div_tq = make_div((unsigned)p.tiles_q);
@@ -1129,6 +1131,10 @@ int dcnv4_set_option(const char *key, int value)
     }
     if (!strcmp(key, "fwd_single") && value >= 0 && value <= 2) {
         g_opt.fwd_single = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "batch_order") && value >= 0 && value <= 2) {
+        g_opt.batch_order = value;
         return DCNV4_OK;
     }
     if (!strcmp(key, "wg_per_cu") && value >= 0 && value <= 16) {
