@@ -651,7 +651,7 @@ int device_cus()
 }
 
 bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, bool with_slices,
-                 TGeo *out, double *cost_out = nullptr)
+                 int chan_slices, TGeo *out, double *cost_out = nullptr)
 {
     const int es = esize(q.dtype);
     // per-wave LDS slices for the 27 offset/mask values of 64 pixels (grad_offset/grad_mask pass only)
@@ -696,7 +696,7 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
             const long long b_full = (R * Q + 63) / 64, b_last = (Rlast * Q + 63) / 64;
             const double rounds_img = tiles_q * ((bands - 1) * (double)((b_full + waves - 1) / waves) +
                                                  (double)((b_last + waves - 1) / waves) + (nbuf == 1 && !locks ? 6.0 : 4.0) * bands);
-            const long long tiles = (long long)q.N * q.G * bands * tiles_q;
+            const long long tiles = (long long)q.N * q.G * chan_slices * bands * tiles_q;
             const double per_tile = rounds_img / (double)(bands * tiles_q);
             const double cost = (double)((tiles + cus - 1) / cus) * per_tile;
             if (cost < best_cost - 1e-9) {
@@ -721,9 +721,14 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
 
 // `mode`: kTiledGradX has a single LDS rectangle of Cg fp32 per pixel plus one lock dword per pixel;
 // kTiledGradOM additionally keeps per-wave slices for the offset/mask values.
-int make_tgeo(const Problem &q, int threads, int mode, TGeo *out)
+int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel = 0)
 {
     const bool gradx = mode == kTiledGradX, with_slices = mode == kTiledGradOM;
+    // a group wider than the kernel's channel run is cut into slices that are tiles of their own
+    const int cgk = cg_kernel ? cg_kernel : q.Cg;
+    if (q.Cg % cgk != 0 || (with_slices && cgk != q.Cg))
+        return DCNV4_ERR_UNSUPPORTED;
+    const int chan_slices = q.Cg / cgk;
     Geo base;
     int rc = make_geo(q, 1, &base);          // shares the 32-bit offset validation
     if (rc)
@@ -735,9 +740,9 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out)
     const int halo = g_opt.halo ? g_opt.halo : (gradx ? kDefaultHaloGradX : kDefaultHalo);
     int lds = (g_opt.lds_kb ? g_opt.lds_kb : kDefaultLdsKb) * 1024;
     if (lds > kMaxLdsBytes) lds = kMaxLdsBytes;
-    const int pb = q.Cg * esize(q.dtype);
+    const int pb = cgk * esize(q.dtype);
     if (gradx) {
-        if (!choose_tile(q, threads, halo, lds, 1, q.Cg * 4, true, false, &p))
+        if (!choose_tile(q, threads, halo, lds, 1, cgk * 4, true, false, chan_slices, &p))
             return DCNV4_ERR_UNSUPPORTED;
         p.nbuf = 1;
     } else {
@@ -747,8 +752,8 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out)
         TGeo one;
         memset(&one, 0, sizeof(one));
         double cost2 = 0, cost1 = 0;
-        const bool ok2 = g_opt.fwd_single != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, with_slices, &p, &cost2);
-        const bool ok1 = g_opt.fwd_single != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, with_slices, &one, &cost1);
+        const bool ok2 = g_opt.fwd_single != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, with_slices, chan_slices, &p, &cost2);
+        const bool ok1 = g_opt.fwd_single != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, with_slices, chan_slices, &one, &cost1);
         if (!ok2 && !ok1)
             return DCNV4_ERR_UNSUPPORTED;
         if (!ok2 || (ok1 && cost1 < cost2)) {
@@ -766,7 +771,7 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out)
     p.sh = q.sh; p.sw = q.sw; p.ph = q.ph; p.pw = q.pw; p.dh = q.dh; p.dw = q.dw;
     p.scale = q.scale;
     p.dmax = base.dmax;
-    const long long nblocks = (long long)q.N * p.tiles_per_img * q.G;
+    const long long nblocks = (long long)q.N * p.tiles_per_img * q.G * chan_slices;
     if (nblocks >= (1LL << 30))
         return DCNV4_ERR_UNSUPPORTED;
     p.nblocks = (int)nblocks;
@@ -774,6 +779,9 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out)
     p.remap = g_opt.xcd_remap;
     p.blocked = g_opt.batch_order ? g_opt.batch_order == 2 : gradx;
     p.div_g = make_div((unsigned)q.G);
+    p.div_s = make_div((unsigned)chan_slices);
+    p.slices = chan_slices;
+    p.group_bytes = q.Cg * esize(q.dtype);
     p.div_tpi = make_div((unsigned)p.tiles_per_img);
     p.div_tq = make_div((unsigned)p.tiles_q);
     p.div_q = make_div((unsigned)p.Q);
@@ -796,7 +804,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
 {
     TGeo p;
     constexpr bool kGradX = MODE == kTiledGradX;
-    int rc = make_tgeo(q, THREADS, MODE, &p);
+    int rc = make_tgeo(q, THREADS, MODE, &p, CG);
     if (rc)
         return rc;
     // a tile of one or two 64-pixel batches leaves most of the workgroup's waves idle and pays the
@@ -870,12 +878,12 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
                 // An image of one or two batches: one-wave workgroups, eight to a compute unit, so that
                 // no wave idles while another works (beats the direct kernel on 7x7 maps).
                 TGeo tiny;
-                if (make_tgeo(q, 64, kTiledFwd, &tiny) == DCNV4_OK && tiny.tiles_per_img == 1 && tiny.R * tiny.Q <= 128)
+                if (make_tgeo(q, 64, kTiledFwd, &tiny, CG) == DCNV4_OK && tiny.tiles_per_img == 1 && tiny.R * tiny.Q <= 128)
                     return launch_tiled<T, CG, 64, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0, true);
             }
             if (g_opt.fwd_threads == 0) {
                 TGeo probe;
-                if (make_tgeo(q, 256, kTiledFwd, &probe) == DCNV4_OK && probe.tiles_per_img == 1 &&
+                if (make_tgeo(q, 256, kTiledFwd, &probe, CG) == DCNV4_OK && probe.tiles_per_img == 1 &&
                     probe.R * probe.Q <= 16 * 64)
                     return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
             }
@@ -890,10 +898,16 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
 template <typename T>
 int dispatch_fwd_tiled_cg(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
+    constexpr int kWidest = 64 / (int)sizeof(T);     // channels of a 64-byte pixel: the widest run a lane keeps
     switch (q.Cg) {
     case 8: return dispatch_fwd_tiled<T, 8>(x, off, msk, y, q, s);
     case 16: return dispatch_fwd_tiled<T, 16>(x, off, msk, y, q, s);
-    case 32: return dispatch_fwd_tiled<T, 32>(x, off, msk, y, q, s);
+    case 32:
+    case 64:
+        // wider groups go through in slices of 64 bytes (same offsets and mask, own channels)
+        if (q.Cg <= kWidest)
+            return dispatch_fwd_tiled<T, 32>(x, off, msk, y, q, s);
+        return dispatch_fwd_tiled<T, kWidest>(x, off, msk, y, q, s);
     }
     return DCNV4_ERR_UNSUPPORTED;
 }

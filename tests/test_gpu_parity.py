@@ -157,15 +157,14 @@ def test_forward_tuning_variants_agree_with_oracle(opts):
     far samples) over tile shapes from tiny to whole-image, all against the oracle."""
     cases = [Config("v", N=3, H=20, W=23, C=64, G=4), Config("v32", N=2, H=11, W=10, C=64, G=2),
              Config("vs2", N=2, H=21, W=17, C=32, G=2, stride=2, pad=2, dilation=2, sigma=3.0),
-             Config("vwide", N=1, H=9, W=70, C=48, G=3, sigma=5.0)]
+             Config("vwide", N=1, H=9, W=70, C=48, G=3, sigma=5.0),
+             Config("v64", N=2, H=13, W=12, C=192, G=3, sigma=3.0)]       # wide groups: channel slices
     ran = 0
     try:
         for k, v in opts.items():
             dcn.dcnv4_set_option(k, v)
         for cfg in cases:
             for dtype in ("f32", "f16"):
-                if opts.get("fwd_path") == 2 and cfg.Cg * (2 if dtype == "f16" else 4) > 64:
-                    continue                      # staged kernel is built for pixels of up to 64 bytes
                 try:
                     check_forward(cfg, dtype, seed=5)
                 except dcn.Dcnv4Error as e:
