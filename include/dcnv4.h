@@ -75,7 +75,9 @@ int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y,
  *   grad_x      += m_k * corner weight * gy[c]   at the in-image neighbours
  * Overwrites all three outputs; grad_x is zero-filled on `stream` first.  Sums are fp32; in F16
  * grad_offset/grad_mask are rounded once, grad_x receives its per-tile fp32 sums through packed
- * fp16 atomics (a pixel is touched by the few tiles that reach it). */
+ * fp16 atomics (a pixel is touched by the few tiles that reach it).  With Cg 32 or 64 (fp32) the
+ * group's channels are processed in slices and grad_offset/grad_mask are summed with fp32 atomics,
+ * so their last bits can differ between runs, like grad_x's. */
 int dcnv4_backward(const void *x, const void *offset, const void *mask, const void *grad_y,
                    void *grad_x, void *grad_offset, void *grad_mask,
                    int N, int H, int W, int G, int Cg,

@@ -456,11 +456,18 @@ __global__ __launch_bounds__(kThreads) void dcnv4_bwd_kernel(const float *__rest
         gm[e] = tile_msk[e];
 }
 
-__global__ __launch_bounds__(kThreads) void dcnv4_zero_kernel(u32x4 *__restrict__ dst, long long n16)
+// Zero-fill of `bytes` bytes (a multiple of 4) at a 16-byte aligned address: 128-bit stores, then the
+// last few dwords one by one.  A kernel rather than a memset node, so that a call can be captured
+// into a graph.
+__global__ __launch_bounds__(kThreads) void dcnv4_zero_kernel(u32x4 *__restrict__ dst, long long bytes)
 {
+    const long long n16 = bytes / 16;
     const u32x4 z = {0u, 0u, 0u, 0u};
     for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (long long)gridDim.x * kThreads)
         dst[i] = z;
+    const int tail = (int)((bytes - n16 * 16) / 4);
+    if (blockIdx.x == 0 && (int)threadIdx.x < tail)
+        reinterpret_cast<unsigned *>(dst + n16)[threadIdx.x] = 0u;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -726,7 +733,8 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
     const bool gradx = mode == kTiledGradX, with_slices = mode == kTiledGradOM;
     // a group wider than the kernel's channel run is cut into slices that are tiles of their own
     const int cgk = cg_kernel ? cg_kernel : q.Cg;
-    if (q.Cg % cgk != 0 || (with_slices && cgk != q.Cg))
+    // (the grad_offset/grad_mask pass can combine slices only in fp32, where it adds them up atomically)
+    if (q.Cg % cgk != 0 || (with_slices && cgk != q.Cg && q.dtype != DCNV4_F32))
         return DCNV4_ERR_UNSUPPORTED;
     const int chan_slices = q.Cg / cgk;
     Geo base;
@@ -938,10 +946,10 @@ int launch_bwd(const void *x, const void *off, const void *msk, const void *gy, 
     int rc = make_geo(q, CG / CPT, &p);
     if (rc)
         return rc;
-    const long long n16 = (long long)q.N * p.x_img_bytes / 16;    // C*4 bytes per pixel is a multiple of 16
-    long long zb = (n16 + kThreads - 1) / kThreads;
+    const long long zbytes = (long long)q.N * p.x_img_bytes;
+    long long zb = (zbytes / 16 + kThreads - 1) / kThreads;
     if (zb > 8192) zb = 8192;
-    hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)gx, n16);
+    hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)gx, zbytes);
     hipLaunchKernelGGL((dcnv4_bwd_kernel<CG, CPT>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const float *)x,
                        (const float *)off, (const float *)msk, (const float *)gy, (float *)gx, (float *)go,
                        (float *)gm, p);
@@ -978,8 +986,11 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
 {
     // the gather pass keeps 4*Cg inputs and gy per lane: eight waves fit the register file in fp16, four in fp32
     constexpr int THREADS = sizeof(T) == 2 ? 512 : 256;
+    // CG is the kernels' channel run; a wider group (q.Cg) goes through as q.Cg / CG slices whose
+    // grad_offset/grad_mask parts are added up in zero-filled outputs
+    const bool sliced = q.Cg != CG;
     TGeo probe;
-    int rc = make_tgeo(q, THREADS, kTiledGradOM, &probe);
+    int rc = make_tgeo(q, THREADS, kTiledGradOM, &probe, CG);
     if (rc)
         return rc;
     // (for fp16 there is no other backward, so the tile-size heuristic does not apply)
@@ -987,16 +998,22 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     if (!any_size && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
     const bool gx512 = g_opt.gx_threads != 256;      // eight waves hide the lock round trips better than four
-    rc = make_tgeo(q, gx512 ? 512 : 256, kTiledGradX, &probe);
+    rc = make_tgeo(q, gx512 ? 512 : 256, kTiledGradX, &probe, CG);
     if (rc)
         return rc;
     if (!any_size && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
-    const long long n16 = (long long)q.N * probe.x_img_bytes / 16;
-    long long zb = (n16 + kThreads - 1) / kThreads;
-    if (zb > 8192) zb = 8192;
-    hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)gx, n16);
-    // (the tile-size heuristic was applied above, to both geometries)
+    auto zero = [&](void *ptr, long long bytes) {
+        long long zb = (bytes / 16 + kThreads - 1) / kThreads;
+        if (zb > 8192) zb = 8192;
+        if (zb < 1) zb = 1;
+        hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)ptr, bytes);
+    };
+    zero(gx, (long long)q.N * probe.x_img_bytes);
+    if (sliced) {
+        zero(go, (long long)q.N * probe.off_img_bytes);
+        zero(gm, (long long)q.N * probe.msk_img_bytes);
+    }
     rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
     if (rc == DCNV4_OK)
         rc = gx512 ? launch_tiled<T, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
@@ -1090,7 +1107,7 @@ int dcnv4_backward(const void *x, const void *offset, const void *mask, const vo
         rc = DCNV4_ERR_UNSUPPORTED;
         if (Cg == 8)
             rc = launch_bwd_tiled<float, 8>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
-        else if (Cg == 16)
+        else if (Cg == 16 || Cg == 32 || Cg == 64)     // wider groups: 64-byte channel slices
             rc = launch_bwd_tiled<float, 16>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.bwd_path == 2)
             return rc;
