@@ -106,7 +106,7 @@ long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
  *                 between tiles), 0 = one when that holds a whole image and two would need bands
  *   "wg_per_cu"   persistent workgroups per compute unit of the staged kernels (1..16, as far as LDS
  *                 allows); default 8 / 2 / 1 for the one- / four- / eight-wave forward, else 1
- *   "gx_threads"  workgroup size of the staged grad_x kernel (256 or 512)
+ *   "gx_threads"  workgroup size of the staged grad_x kernel (256, 512 or 768)
  *   "halo"        displacement in pixels that the staged window allows for (default 6);
  *                 samples beyond it are still exact, they take the global path
  *   "lds_kb"      LDS budget per workgroup of the staged kernel (8..160)

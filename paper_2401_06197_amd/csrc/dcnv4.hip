@@ -997,8 +997,9 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     const bool any_size = g_opt.bwd_path == 2 || sizeof(T) == 2;
     if (!any_size && probe.R * probe.Q < 128)
         return DCNV4_ERR_UNSUPPORTED;
-    const bool gx512 = g_opt.gx_threads != 256;      // eight waves hide the lock round trips better than four
-    rc = make_tgeo(q, gx512 ? 512 : 256, kTiledGradX, &probe, CG);
+    // the grad_x pass is a chain of LDS round trips per lane: twelve waves hide them best (measured)
+    const int gxt = g_opt.gx_threads ? g_opt.gx_threads : 768;
+    rc = make_tgeo(q, gxt, kTiledGradX, &probe, CG);
     if (rc)
         return rc;
     if (!any_size && probe.R * probe.Q < 128)
@@ -1016,8 +1017,9 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     }
     rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
     if (rc == DCNV4_OK)
-        rc = gx512 ? launch_tiled<T, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
-                   : launch_tiled<T, CG, 256, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true);
+        rc = gxt == 768   ? launch_tiled<T, CG, 768, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
+             : gxt == 512 ? launch_tiled<T, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
+                          : launch_tiled<T, CG, 256, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true);
     return rc;
 }
 
@@ -1156,7 +1158,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.fwd_path = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "gx_threads") && (value == 0 || value == 256 || value == 512)) {
+    if (!strcmp(key, "gx_threads") && (value == 0 || value == 256 || value == 512 || value == 768)) {
         g_opt.gx_threads = value;
         return DCNV4_OK;
     }
