@@ -110,7 +110,7 @@ long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
  *   "halo"        displacement in pixels that the staged window allows for (default 6);
  *                 samples beyond it are still exact, they take the global path
  *   "lds_kb"      LDS budget per workgroup of the staged kernel (8..160)
- *   "fwd_threads" workgroup size of the staged forward (64, 256 or 512; default by tile size)
+ *   "fwd_threads" workgroup size of the staged forward (64, 256, 512 or 768; default by tile size)
  *   "fwd_cpt"     channels per thread in the direct forward kernel (8 or 16)
  *   "bwd_cpt"     channels per thread in the direct backward kernel (1, 2, 4, 8 or 16)
  *   "xcd_remap"   1 = hand consecutive tiles to one XCD (default), 0 = plain block order

@@ -142,7 +142,7 @@ def test_small_geometries_backward(cfg):
 
 FWD_VARIANTS = [
     {"fwd_path": 1, "fwd_cpt": 8}, {"fwd_path": 1, "fwd_cpt": 16}, {"fwd_path": 1, "xcd_remap": 0},
-    {"fwd_path": 2}, {"fwd_path": 2, "fwd_threads": 512}, {"fwd_path": 2, "xcd_remap": 0},
+    {"fwd_path": 2}, {"fwd_path": 2, "fwd_threads": 512}, {"fwd_path": 2, "fwd_threads": 768}, {"fwd_path": 2, "xcd_remap": 0},
     {"fwd_path": 2, "halo": 1}, {"fwd_path": 2, "halo": 2, "lds_kb": 48}, {"fwd_path": 2, "halo": 12, "lds_kb": 160},
     {"fwd_path": 2, "halo": 3, "lds_kb": 40, "fwd_threads": 256},
     {"fwd_path": 2, "fwd_threads": 256, "wg_per_cu": 3, "lds_kb": 50}, {"fwd_path": 2, "fwd_threads": 512, "wg_per_cu": 1},
