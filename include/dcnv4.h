@@ -106,6 +106,10 @@ long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
  *                 between tiles), 0 = one when that holds a whole image and two would need bands
  *   "wg_per_cu"   persistent workgroups per compute unit of the staged kernels (1..16, as far as LDS
  *                 allows); default 8 / 2 / 1 for the one- / four- / eight-wave forward, else 1
+ *   "gom_coop"    1 = the fp32 grad_offset/grad_mask pass moves its values through per-wave LDS slices
+ *                 even for whole groups (default: each lane reads and writes its own pixel's values)
+ *   "batch_order" how a tile's batches go to the waves in the staged kernels: 1 interleaved, 2 in
+ *                 contiguous runs (default: runs in the grad_x pass, interleaved elsewhere)
  *   "gx_threads"  workgroup size of the staged grad_x kernel (256, 512 or 768)
  *   "halo"        displacement in pixels that the staged window allows for (default 6);
  *                 samples beyond it are still exact, they take the global path

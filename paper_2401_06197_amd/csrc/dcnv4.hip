@@ -482,6 +482,7 @@ struct Options {
     int lds_kb = 0;        // LDS budget per workgroup of the tiled kernel, 0 = default
     int fwd_threads = 0;   // 256 or 512 for the tiled kernel, 0 = default
     int bwd_path = 0;      // 0 auto, 1 direct (global atomics), 2 LDS-tiled
+    int gom_coop = 0;      // 1: the fp32 grad_offset/grad_mask pass goes through LDS slices even for whole groups
     int batch_order = 0;   // 0 default (blocked in grad_x, interleaved elsewhere), 1 interleaved, 2 blocked
     int wg_per_cu = 0;     // persistent workgroups per compute unit (1..4), 0 = default
     int fwd_single = 0;    // rectangle buffers of the staged gather kernels: 0 auto, 1 always two, 2 always one
@@ -821,7 +822,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
         return DCNV4_ERR_UNSUPPORTED;
     const int px_bytes = kGradX ? CG * 4 : CG * (int)sizeof(T);
     const int tail = kGradX ? (p.xtile_bytes / px_bytes) * 4 + 16 : ((p.pitch + kTiledZeroPixelsExtra) * px_bytes + 15) & ~15;
-    const int slices = MODE == kTiledGradOM ? (THREADS / 64) * 64 * 27 * (int)sizeof(T) : 0;
+    const int slices = MODE == kTiledGradOM ? (THREADS / 64) * 64 * 27 * (int)sizeof(T) : 0;     // (not kTiledGradOMDirect)
     const int lds = p.nbuf * p.xtile_bytes + slices + tail;
     if (lds > kMaxLdsBytes)
         return DCNV4_ERR_UNSUPPORTED;
@@ -996,7 +997,8 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     // grad_offset/grad_mask parts are added up in zero-filled outputs
     const bool sliced = q.Cg != CG;
     TGeo probe;
-    int rc = make_tgeo(q, THREADS, kTiledGradOM, &probe, CG);
+    const bool gom_direct = sizeof(T) == 4 && !sliced && g_opt.gom_coop == 0;
+    int rc = make_tgeo(q, gom_direct ? 512 : THREADS, gom_direct ? kTiledGradOMDirect : kTiledGradOM, &probe, CG);
     if (rc)
         return rc;
     // (for fp16 there is no other backward, so the tile-size heuristic does not apply)
@@ -1021,7 +1023,15 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
         zero(go, (long long)q.N * probe.off_img_bytes);
         zero(gm, (long long)q.N * probe.msk_img_bytes);
     }
-    rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
+    if constexpr (sizeof(T) == 4) {
+        // whole fp32 groups: the lanes read and write their own pixels' values, no LDS slices, eight waves
+        if (!sliced && g_opt.gom_coop == 0)
+            rc = launch_tiled<T, CG, 512, kTiledGradOMDirect>(x, off, msk, gy, go, gm, q, s, 1, true);
+        else
+            rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
+    } else {
+        rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
+    }
     if (rc == DCNV4_OK)
         rc = gxt == 768   ? launch_tiled<T, CG, 768, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
              : gxt == 512 ? launch_tiled<T, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
@@ -1170,6 +1180,10 @@ int dcnv4_set_option(const char *key, int value)
     }
     if (!strcmp(key, "fwd_single") && value >= 0 && value <= 2) {
         g_opt.fwd_single = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "gom_coop") && (value == 0 || value == 1)) {
+        g_opt.gom_coop = value;
         return DCNV4_OK;
     }
     if (!strcmp(key, "batch_order") && value >= 0 && value <= 2) {

@@ -184,7 +184,7 @@ BWD_VARIANTS = [
     {"bwd_path": 1}, {"bwd_path": 1, "bwd_cpt": 1}, {"bwd_path": 1, "bwd_cpt": 2},
     {"bwd_path": 1, "bwd_cpt": 4}, {"bwd_path": 1, "bwd_cpt": 8}, {"bwd_path": 1, "bwd_cpt": 16},
     {"bwd_path": 1, "xcd_remap": 0},
-    {"bwd_path": 2}, {"bwd_path": 2, "xcd_remap": 0}, {"bwd_path": 2, "halo": 1}, {"bwd_path": 2, "halo": 3, "lds_kb": 100}, {"bwd_path": 2, "gx_threads": 256, "lds_kb": 110}, {"bwd_path": 2, "gx_threads": 512},
+    {"bwd_path": 2}, {"bwd_path": 2, "xcd_remap": 0}, {"bwd_path": 2, "halo": 1}, {"bwd_path": 2, "halo": 3, "lds_kb": 100}, {"bwd_path": 2, "gx_threads": 256, "lds_kb": 110}, {"bwd_path": 2, "gx_threads": 512}, {"bwd_path": 2, "gom_coop": 1},
     {"bwd_path": 2, "halo": 12}, {"bwd_path": 2, "fwd_single": 2}, {"bwd_path": 2, "fwd_single": 1},
 ]
 
