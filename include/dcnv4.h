@@ -100,18 +100,20 @@ long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
  *                 useful tile fits, else direct
  *   "bwd_path"    1 = one kernel with global atomics for grad_x, 2 = two LDS-staged kernels (gathers
  *                 for grad_offset/grad_mask; LDS-private accumulation of grad_x), 0 = staged where
- *                 it applies (Cg 8 or 16 and a useful tile fits), else the first
+ *                 it applies (Cg up to 16, wider fp32 groups as 64-byte channel slices, and a useful
+ *                 tile fits), else the first
  *   "fwd_single"  LDS rectangle buffers of the staged gather kernels: 1 = always two (the next tile
  *                 streams in during the current one), 2 = always one (bigger rectangle, refilled
- *                 between tiles), 0 = one when that holds a whole image and two would need bands
+ *                 between tiles), 0 = whichever the tile chooser estimates to be cheaper
  *   "wg_per_cu"   persistent workgroups per compute unit of the staged kernels (1..16, as far as LDS
- *                 allows); default 8 / 2 / 1 for the one- / four- / eight-wave forward, else 1
+ *                 allows); default 8 / 2 for the one- / four-wave forward, else 1
  *   "gom_coop"    1 = the fp32 grad_offset/grad_mask pass moves its values through per-wave LDS slices
  *                 even for whole groups (default: each lane reads and writes its own pixel's values)
  *   "batch_order" how a tile's batches go to the waves in the staged kernels: 1 interleaved, 2 in
  *                 contiguous runs (default: runs in the grad_x pass, interleaved elsewhere)
  *   "gx_threads"  workgroup size of the staged grad_x kernel (256, 512 or 768)
- *   "halo"        displacement in pixels that the staged window allows for (default 6);
+ *   "halo"        displacement in pixels that the staged window allows for (default 6, 4 in the grad_x
+ *                 pass; tiles that hold a whole image have no use for it);
  *                 samples beyond it are still exact, they take the global path
  *   "lds_kb"      LDS budget per workgroup of the staged kernel (8..160)
  *   "fwd_threads" workgroup size of the staged forward (64, 256, 512 or 768; default by tile size)
