@@ -729,7 +729,7 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
 
 // `mode`: kTiledGradX has a single LDS rectangle of Cg fp32 per pixel plus one lock dword per pixel;
 // kTiledGradOM additionally keeps per-wave slices for the offset/mask values.
-int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel = 0)
+int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel = 0, int want_nbuf = 0)
 {
     const bool gradx = mode == kTiledGradX, with_slices = mode == kTiledGradOM;
     // a group wider than the kernel's channel run is cut into slices that are tiles of their own
@@ -761,8 +761,9 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
         TGeo one;
         memset(&one, 0, sizeof(one));
         double cost2 = 0, cost1 = 0;
-        const bool ok2 = g_opt.fwd_single != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, with_slices, chan_slices, &p, &cost2);
-        const bool ok1 = g_opt.fwd_single != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, with_slices, chan_slices, &one, &cost1);
+        const int pick = g_opt.fwd_single ? g_opt.fwd_single : want_nbuf == 1 ? 2 : want_nbuf == 2 ? 1 : 0;
+        const bool ok2 = pick != 2 && choose_tile(q, threads, halo, lds, 2, pb, false, with_slices, chan_slices, &p, &cost2);
+        const bool ok1 = pick != 1 && choose_tile(q, threads, halo, lds, 1, pb, false, with_slices, chan_slices, &one, &cost1);
         if (!ok2 && !ok1)
             return DCNV4_ERR_UNSUPPORTED;
         if (!ok2 || (ok1 && cost1 < cost2)) {
@@ -809,11 +810,11 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
 // kernel-name record).
 template <typename T, int CG, int THREADS, int MODE>
 int launch_tiled(const void *x, const void *off, const void *msk, const void *gy, void *o1, void *o2,
-                 const Problem &q, hipStream_t s, int which, bool any_tile_size)
+                 const Problem &q, hipStream_t s, int which, bool any_tile_size, int want_nbuf = 0, int want_per_cu = 0)
 {
     TGeo p;
     constexpr bool kGradX = MODE == kTiledGradX;
-    int rc = make_tgeo(q, THREADS, MODE, &p, CG);
+    int rc = make_tgeo(q, THREADS, MODE, &p, CG, want_nbuf);
     if (rc)
         return rc;
     // a tile of one or two 64-pixel batches leaves most of the workgroup's waves idle and pays the
@@ -840,7 +841,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
         return DCNV4_ERR_LAUNCH;
     // several persistent workgroups per compute unit when their LDS and registers fit: their tile
     // switches (barrier, drained pipeline) then overlap with each other's work
-    int per_cu = g_opt.wg_per_cu ? g_opt.wg_per_cu : (MODE != kTiledFwd || CG * sizeof(T) >= 64 ? 1 : THREADS == 256 ? 2 : THREADS == 64 ? 8 : 1);
+    int per_cu = g_opt.wg_per_cu ? g_opt.wg_per_cu : want_per_cu ? want_per_cu : (MODE != kTiledFwd || CG * sizeof(T) >= 64 ? 1 : THREADS == 256 ? 2 : THREADS == 64 ? 8 : 1);
     while (per_cu > 1 && (per_cu * lds > kMaxLdsBytes || per_cu * THREADS > 2048))
         --per_cu;
     const int slots = cus * per_cu;
@@ -879,10 +880,12 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
         if (g_opt.fwd_threads == 256)
             return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
         if constexpr (CG * sizeof(T) < 64) {
-            // Small whole-image tiles: two four-wave workgroups per compute unit, whose tile
-            // switches overlap with each other's work, beat one eight-wave workgroup.
+            // Small whole-image tiles: several four-wave workgroups per compute unit, whose tile
+            // switches overlap with each other's work, beat one big workgroup.
             if (g_opt.fwd_threads == 64)
                 return launch_fwd_tiled<T, CG, 64>(x, off, msk, y, q, s);
+            if (g_opt.fwd_threads == 128)
+                return launch_fwd_tiled<T, CG, 128>(x, off, msk, y, q, s);
             if (g_opt.fwd_threads == 768)
                 return launch_fwd_tiled<T, CG, 768>(x, off, msk, y, q, s);
             if (g_opt.fwd_threads == 0 && g_opt.fwd_path != 1) {
@@ -894,9 +897,12 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
             }
             if (g_opt.fwd_threads == 0) {
                 TGeo probe;
-                if (make_tgeo(q, 256, kTiledFwd, &probe, CG) == DCNV4_OK && probe.tiles_per_img == 1 &&
+                // (one rectangle buffer each: with several workgroups on the unit, one computes while
+                // another refills, and the halved LDS lets three of them in)
+                if (make_tgeo(q, 256, kTiledFwd, &probe, CG, 1) == DCNV4_OK && probe.tiles_per_img == 1 &&
                     probe.R * probe.Q <= 16 * 64)
-                    return launch_fwd_tiled<T, CG, 256>(x, off, msk, y, q, s);
+                    return launch_tiled<T, CG, 256, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0,
+                                                               g_opt.fwd_path == 2, 1, 3);
             }
             if (g_opt.fwd_threads == 512)
                 return launch_fwd_tiled<T, CG, 512>(x, off, msk, y, q, s);
@@ -1206,7 +1212,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.lds_kb = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 64 || value == 256 || value == 512 || value == 768)) {
+    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 64 || value == 128 || value == 256 || value == 512 || value == 768)) {
         g_opt.fwd_threads = value;
         return DCNV4_OK;
     }
