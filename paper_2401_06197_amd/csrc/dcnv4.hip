@@ -29,6 +29,8 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 // n / d for 0 <= n < 2^31 as mulhi + add + shift (d >= 1), constants made on the host.
@@ -201,6 +203,20 @@ __device__ __forceinline__ Tap tap_geometry(float dY, float dX, int base_h, int 
                        p.pix_bytes);
 }
 
+__device__ __forceinline__ int cvt_floor_i32(float v)
+{
+    int r;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(r) : "v"(v));       // floor, saturating, NaN -> 0
+    return r;
+}
+
+__device__ __forceinline__ int med3i(int v, int lo, int hi)     // clamp to [lo, hi] in one instruction
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
+
 // channel c of a 16-byte unit, widened to fp32
 template <typename T> __device__ __forceinline__ float unit_get(const u32x4 &v, int c);
 template <> __device__ __forceinline__ float unit_get<_Float16>(const u32x4 &v, int c)
@@ -328,6 +344,7 @@ __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict
 }
 
 #include "dcnv4_tiled.inc"
+#include "dcnv4_ring.inc"
 
 // ------------------------------------------------------------------------------------------
 // Backward (chain rule on Eq. 1), fp32, in one pass with grad_x added straight to memory; used
@@ -933,9 +950,165 @@ int dispatch_fwd_tiled_cg(const void *x, const void *off, const void *msk, void 
     return DCNV4_ERR_UNSUPPORTED;
 }
 
+// ---- forward out of a ring of record rows (fp16, 16 channels per group, full-width tiles) ----
+// Chooses how many record rows the LDS ring holds and the row halo: a host-side walk over the
+// rounds of one workgroup (same arithmetic as the kernel's) finds the largest halo, up to 8 rows,
+// for which the rows of two consecutive rounds always fit the ring, and checks that one round can
+// stage the rows the next one adds.  Returns DCNV4_ERR_UNSUPPORTED where the kernel does not apply.
+int make_rgeo(const Problem &q, int waves, int grid_wgs, RGeo *out)
+{
+    if (q.dtype != DCNV4_F16 || q.Cg != 16)
+        return DCNV4_ERR_UNSUPPORTED;
+    Geo base;
+    int rc = make_geo(q, 1, &base);
+    if (rc)
+        return rc;
+    RGeo p;
+    memset(&p, 0, sizeof(p));
+    const long long C = (long long)q.G * q.Cg;
+    const long long xbytes = (long long)q.N * q.H * q.W * C * 2;
+    const long long pgi = (long long)q.Ho * q.Wo * q.G;
+    if (xbytes >= (1LL << 31) || pgi >= 0x1000000 || (long long)q.N * q.G >= (1LL << 24))
+        return DCNV4_ERR_UNSUPPORTED;
+    p.H = q.H; p.W = q.W; p.Ho = q.Ho; p.Wo = q.Wo; p.G = q.G;
+    p.sh = q.sh; p.sw = q.sw; p.ph = q.ph; p.pw = q.pw; p.dh = q.dh; p.dw = q.dw;
+    p.scale = q.scale;
+    p.dmax = base.dmax;
+    p.pitch = q.W + 4;
+    p.VR = q.H + 3;
+    p.npx = q.Ho * q.Wo;
+    p.B = (p.npx + 63) / 64;
+    const int lds_budget = (g_opt.lds_kb ? g_opt.lds_kb : 160) * 1024 - 128;
+    p.ring = lds_budget / (p.pitch * kRingRecBytes);
+    p.ntiles = q.N * q.G;
+    p.tiles_per_xcd = (p.ntiles + kXcds - 1) / kXcds;
+    p.remap = g_opt.xcd_remap;
+    p.cbn = (p.pitch + 31) / 32;
+    p.max_groups_round = kRingMaxTasks * waves / p.cbn;
+    if (p.ring < 2 * kRingTaskRows || p.max_groups_round < 1)
+        return DCNV4_ERR_UNSUPPORTED;
+    // tiles the busiest workgroup walks
+    int S;
+    if (p.remap) {
+        const int per = grid_wgs / kXcds;
+        S = (p.tiles_per_xcd + per - 1) / per;
+    } else {
+        S = (p.ntiles + grid_wgs - 1) / grid_wgs;
+    }
+    const int RK = kRingTaskRows;
+    if (p.ring > (S * p.VR + RK - 1) / RK * RK)
+        p.ring = (S * p.VR + RK - 1) / RK * RK;      // no use for more rows than the workgroup ever stages
+    const int NB = S * p.B;
+    auto need = [&](int gb, int hr, int *lo, int *hi) {
+        const int s = gb / p.B, b = gb - s * p.B;
+        const int q0 = b * 64, q1 = q0 + 63 < p.npx - 1 ? q0 + 63 : p.npx - 1;
+        const int oa = q0 / p.Wo, ob = q1 / p.Wo;
+        int l = oa * p.sh - p.ph - hr, h = ob * p.sh - p.ph + 2 * p.dh + hr;
+        l = l < -2 ? -2 : l > p.H ? p.H : l;
+        h = h > p.H ? p.H : h < -2 ? -2 : h;
+        *lo = s * p.VR + 2 + l;
+        *hi = s * p.VR + 2 + h;
+    };
+    const int rounds = (NB + waves - 1) / waves;
+    const int sim_rounds = rounds < 4096 ? rounds : 4096;
+    int best = -1;
+    const int hr_cap = g_opt.halo ? g_opt.halo : 8;
+    for (int hr = hr_cap; hr >= 2 && best < 0; --hr) {
+        bool ok = true;
+        for (int t = 0; t < sim_rounds && ok; ++t) {
+            int lo_first, hi_dummy, lo_dummy, hi_next, hi_this;
+            need(t * waves, hr, &lo_first, &hi_dummy);
+            const int last_this = (t + 1) * waves < NB ? (t + 1) * waves - 1 : NB - 1;
+            const int last_next = (t + 2) * waves < NB ? (t + 2) * waves - 1 : NB - 1;
+            need(last_this, hr, &lo_dummy, &hi_this);
+            need(last_next, hr, &lo_dummy, &hi_next);
+            const int g_this = (hi_this + RK) / RK, g_next = (hi_next + RK) / RK;    // row groups staged by then
+            if (g_next * RK > lo_first + p.ring)
+                ok = false;                                   // two rounds' rows do not fit
+            if (t == 0 && g_this * RK > p.ring)
+                ok = false;
+            if (g_next - g_this > p.max_groups_round)
+                ok = false;                                   // one round cannot stage the next one's rows
+        }
+        if (ok)
+            best = hr;
+    }
+    if (best < 0)
+        return DCNV4_ERR_UNSUPPORTED;
+    p.hr = best;
+    p.div_g = make_div((unsigned)q.G);
+    p.div_wo = make_div((unsigned)q.Wo);
+    p.div_cbn = make_div((unsigned)p.cbn);
+    p.div_vr = make_div((unsigned)p.VR);
+    p.div_ring = make_div((unsigned)p.ring);
+    p.div_b = make_div((unsigned)p.B);
+    p.x_bytes = (int)xbytes;
+    p.x_img_bytes = base.x_img_bytes;
+    p.y_img_bytes = base.y_img_bytes;
+    p.row_bytes = base.row_bytes;
+    p.pix_bytes = base.pix_bytes;
+    p.off_img_bytes = (int)(pgi * 36);
+    p.msk_img_bytes = (int)(pgi * 18);
+    *out = p;
+    return DCNV4_OK;
+}
+
+template <int WAVES>
+int launch_ring_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    const int cus = device_cus();
+    if (cus <= 0)
+        return DCNV4_ERR_LAUNCH;
+    const long long ntiles = (long long)q.N * q.G;
+    const long long tiles_per_xcd = (ntiles + kXcds - 1) / kXcds;
+    unsigned grid;
+    if (g_opt.xcd_remap) {
+        const long long per = cus / kXcds < tiles_per_xcd ? cus / kXcds : tiles_per_xcd;
+        grid = (unsigned)(per * kXcds);
+    } else {
+        grid = (unsigned)(cus < ntiles ? cus : ntiles);
+    }
+    RGeo p;
+    int rc = make_rgeo(q, WAVES, (int)grid, &p);
+    if (rc)
+        return rc;
+    const int lds = p.ring * p.pitch * kRingRecBytes + 128;
+    if (lds > kMaxLdsBytes)
+        return DCNV4_ERR_UNSUPPORTED;
+    auto kern = dcnv4_ring_fwd_kernel<WAVES>;
+    static int granted = 0;
+    if (lds > 64 * 1024 && lds > granted) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds) != hipSuccess)
+            return DCNV4_ERR_LAUNCH;
+        granted = lds;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), lds, s, (const _Float16 *)x, (const _Float16 *)off,
+                       (const _Float16 *)msk, (_Float16 *)y, p);
+    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_ring_fwd_kernel<%d>", WAVES);
+    return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
+int dispatch_ring_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    switch (g_opt.fwd_threads) {
+    case 768: return launch_ring_fwd<12>(x, off, msk, y, q, s);
+    case 640: return launch_ring_fwd<10>(x, off, msk, y, q, s);
+    case 256: return launch_ring_fwd<4>(x, off, msk, y, q, s);
+    default: return launch_ring_fwd<8>(x, off, msk, y, q, s);
+    }
+}
+
 template <typename T>
 int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
+    if (sizeof(T) == 2 && (g_opt.fwd_path == 0 || g_opt.fwd_path == 3)) {
+        const int rc = dispatch_ring_fwd(x, off, msk, y, q, s);
+        if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 3)
+            return rc;
+    }
+    if (g_opt.fwd_path == 3)
+        return DCNV4_ERR_UNSUPPORTED;
     if (g_opt.fwd_path != 1) {
         const int rc = dispatch_fwd_tiled_cg<T>(x, off, msk, y, q, s);
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 2)
@@ -1176,7 +1349,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.xcd_remap = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "fwd_path") && value >= 0 && value <= 2) {
+    if (!strcmp(key, "fwd_path") && value >= 0 && value <= 3) {
         g_opt.fwd_path = value;
         return DCNV4_OK;
     }
@@ -1212,7 +1385,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.lds_kb = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 64 || value == 128 || value == 256 || value == 512 || value == 768)) {
+    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 64 || value == 128 || value == 256 || value == 512 || value == 640 || value == 768)) {
         g_opt.fwd_threads = value;
         return DCNV4_OK;
     }

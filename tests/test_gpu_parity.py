@@ -344,6 +344,53 @@ def test_forward_and_backward_replay_correctly_from_a_hip_graph():
         close(f"graph{rep}/grad_mask", grads[2].cpu().numpy(), rgm, TOL["f32"])
 
 
+# ------------------------------------------------------------------ forward out of the ring of record rows
+RING_CASES = [
+    Config("r_c1", N=1, H=14, W=14, C=64, G=4),
+    Config("r_rag", N=3, H=13, W=11, C=48, G=3),
+    Config("r_tall", N=2, H=75, W=9, C=32, G=2, sigma=3.0),
+    Config("r_wide", N=1, H=9, W=70, C=48, G=3, sigma=5.0),
+    Config("r_s2", N=2, H=21, W=17, C=32, G=2, stride=2, pad=2, dilation=2, sigma=3.0),
+    Config("r_s3", N=2, H=17, W=19, C=64, G=4, stride=3, pad=2, dilation=2, offset_scale=0.5),
+    Config("r_pad0", N=1, H=9, W=9, C=16, G=1, pad=0),
+    Config("r_pad5", N=1, H=14, W=14, C=32, G=2, pad=5, sigma=1.0),
+    Config("r_1px", N=2, H=1, W=1, C=16, G=1),
+    Config("r_row", N=1, H=1, W=37, C=32, G=2),
+    Config("r_col", N=1, H=41, W=1, C=32, G=2),
+    Config("r_tiny_many", N=9, H=7, W=7, C=1024, G=64),
+    Config("r_far", N=2, H=30, W=24, C=32, G=2, sigma=9.0),
+    Config("r_many_tiles", N=40, H=10, W=12, C=160, G=10),
+]
+RING_OPTS = [{}, {"fwd_threads": 256}, {"fwd_threads": 640}, {"fwd_threads": 768}, {"halo": 2}, {"lds_kb": 24},
+             {"lds_kb": 48, "fwd_threads": 768}, {"xcd_remap": 0}, {"lds_kb": 16, "halo": 3, "fwd_threads": 256}]
+
+
+@pytest.mark.parametrize("cfg", RING_CASES, ids=[c.name for c in RING_CASES])
+@pytest.mark.parametrize("opts", RING_OPTS, ids=[",".join(f"{k}={v}" for k, v in o.items()) or "default" for o in RING_OPTS])
+def test_ring_forward_fp16(cfg, opts):
+    """The fp16 forward that gathers from a rolling window of row-pair records (dot products of fp16
+    pairs, fp32 sums), over ring sizes from a few rows to a whole image, every workgroup size, strides,
+    dilations, pads, images smaller than a batch and offsets far beyond the halo."""
+    try:
+        for k, v in opts.items():
+            dcn.dcnv4_set_option(k, v)
+        dcn.dcnv4_set_option("fwd_path", 3)
+        try:
+            check_forward(cfg, "f16", seed=70)
+        except dcn.Dcnv4Error as e:
+            assert e.status == 3 and ("lds_kb" in opts or "halo" in opts)     # ring too small for this image width
+            return
+        assert dcn.dcnv4_last_kernel_name(0).startswith("dcnv4_ring_fwd_kernel<")
+    finally:
+        for k in list(opts) + ["fwd_path"]:
+            dcn.dcnv4_set_option(k, 1 if k == "xcd_remap" else 0)
+
+
+def test_ring_forward_is_the_default_for_fp16_groups_of_16():
+    check_forward(CONFIGS["c1"], "f16")
+    assert dcn.dcnv4_last_kernel_name(0).startswith("dcnv4_ring_fwd_kernel<")
+
+
 def _random_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []

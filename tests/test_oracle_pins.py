@@ -215,7 +215,7 @@ def test_finite_differences_on_tiny_config():
 def test_right_derivative_at_integer_coordinates():
     """At a whole-number coordinate the floor rule makes the derivative the right-hand one:
     a one-sided difference towards +eps matches, even on the row just above the image."""
-    x = np.arange(12, dtype=np.float64).reshape(1, 3, 4, 1) ** 1.5
+    x = (np.arange(12, dtype=np.float64).reshape(1, 3, 4, 1) + 1.0) ** 1.5
     off = np.zeros((1, 3, 4, 1, 9, 2))
     m = np.zeros((1, 3, 4, 1, 9))
     k = 0 * 3 + 0                                       # top-left tap: at output (0,1) it sits at row -1, col 0
@@ -228,7 +228,10 @@ def test_right_derivative_at_integer_coordinates():
         o2 = off.copy(); o2[0, 0, 1, 0, k, comp] += eps
         fd = (np.sum(oracle.forward(x, o2, m)) - base) / eps
         np.testing.assert_allclose(go[0, 0, 1, 0, k, comp], fd, rtol=1e-5, atol=1e-6)
-    assert go[0, 0, 1, 0, k, 1] == 1.3 * x[0, 0, 0, 0] or go[0, 0, 1, 0, k, 1] != 0 or x[0, 0, 0, 0] == 0
+    # worked by hand: on row -1 the value is zero, but moving down by t reaches t * x[row 0, col 0],
+    # so the height derivative is m * x[0, 0] = 1.3 * 1; moving right stays on the zero row
+    assert go[0, 0, 1, 0, k, 1] == pytest.approx(1.3 * 1.0, rel=1e-12)
+    assert go[0, 0, 1, 0, k, 0] == 0.0
 
 
 # ---------------------------------------------------------------- T9/T10: library routine
