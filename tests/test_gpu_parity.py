@@ -361,7 +361,7 @@ RING_CASES = [
     Config("r_far", N=2, H=30, W=24, C=32, G=2, sigma=9.0),
     Config("r_many_tiles", N=40, H=10, W=12, C=160, G=10),
 ]
-RING_OPTS = [{}, {"fwd_threads": 256}, {"fwd_threads": 640}, {"fwd_threads": 768}, {"halo": 2}, {"lds_kb": 24},
+RING_OPTS = [{}, {"fwd_threads": 256}, {"fwd_threads": 768}, {"halo": 2}, {"lds_kb": 24},
              {"lds_kb": 48, "fwd_threads": 768}, {"xcd_remap": 0}, {"lds_kb": 16, "halo": 3, "fwd_threads": 256}]
 
 
