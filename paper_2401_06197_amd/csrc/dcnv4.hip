@@ -955,7 +955,7 @@ int dispatch_fwd_tiled_cg(const void *x, const void *off, const void *msk, void 
 // rounds of one workgroup (same arithmetic as the kernel's) finds the largest halo, up to 8 rows,
 // for which the rows of two consecutive rounds always fit the ring, and checks that one round can
 // stage the rows the next one adds.  Returns DCNV4_ERR_UNSUPPORTED where the kernel does not apply.
-int make_rgeo(const Problem &q, int waves, int max_tasks, int grid_wgs, RGeo *out)
+int make_rgeo(const Problem &q, int waves, int grid_wgs, RGeo *out)
 {
     if (q.dtype != DCNV4_F16 || q.Cg != 16)
         return DCNV4_ERR_UNSUPPORTED;
@@ -978,13 +978,13 @@ int make_rgeo(const Problem &q, int waves, int max_tasks, int grid_wgs, RGeo *ou
     p.VR = q.H + 3;
     p.npx = q.Ho * q.Wo;
     p.B = (p.npx + 63) / 64;
-    const int lds_budget = (g_opt.lds_kb ? g_opt.lds_kb : 160) * 1024 - 128 - 128;
+    const int lds_budget = (g_opt.lds_kb ? g_opt.lds_kb : 160) * 1024 - 128;
     p.ring = lds_budget / (p.pitch * kRingRecBytes);
     p.ntiles = q.N * q.G;
     p.tiles_per_xcd = (p.ntiles + kXcds - 1) / kXcds;
     p.remap = g_opt.xcd_remap;
     p.cbn = (p.pitch + 31) / 32;
-    p.max_groups_round = max_tasks * waves / p.cbn;
+    p.max_groups_round = kRingMaxTasks * waves / p.cbn;
     if (p.ring < 2 * kRingTaskRows || p.max_groups_round < 1)
         return DCNV4_ERR_UNSUPPORTED;
     // tiles the busiest workgroup walks
@@ -1053,7 +1053,7 @@ int make_rgeo(const Problem &q, int waves, int max_tasks, int grid_wgs, RGeo *ou
     return DCNV4_OK;
 }
 
-template <int WAVES, int MAXT>
+template <int WAVES>
 int launch_ring_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
     const int cus = device_cus();
@@ -1069,13 +1069,13 @@ int launch_ring_fwd(const void *x, const void *off, const void *msk, void *y, co
         grid = (unsigned)(cus < ntiles ? cus : ntiles);
     }
     RGeo p;
-    int rc = make_rgeo(q, WAVES, MAXT, (int)grid, &p);
+    int rc = make_rgeo(q, WAVES, (int)grid, &p);
     if (rc)
         return rc;
-    const int lds = p.ring * p.pitch * kRingRecBytes + 128 + 128;
+    const int lds = p.ring * p.pitch * kRingRecBytes + 128;
     if (lds > kMaxLdsBytes)
         return DCNV4_ERR_UNSUPPORTED;
-    auto kern = dcnv4_ring_fwd_kernel<WAVES, MAXT>;
+    auto kern = dcnv4_ring_fwd_kernel<WAVES>;
     static int granted = 0;
     if (lds > 64 * 1024 && lds > granted) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1085,27 +1085,17 @@ int launch_ring_fwd(const void *x, const void *off, const void *msk, void *y, co
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), lds, s, (const _Float16 *)x, (const _Float16 *)off,
                        (const _Float16 *)msk, (_Float16 *)y, p);
-    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_ring_fwd_kernel<%d, %d>", WAVES, MAXT);
+    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_ring_fwd_kernel<%d>", WAVES);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
-}
-
-// one staging task per wave and round where that keeps up with the rows a round consumes (wide
-// images), up to three where an image row is a small part of a task's 32 columns
-template <int WAVES>
-int launch_ring_fwd_tasks(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
-{
-    const int rc = launch_ring_fwd<WAVES, 1>(x, off, msk, y, q, s);
-    if (rc != DCNV4_ERR_UNSUPPORTED)
-        return rc;
-    return launch_ring_fwd<WAVES, kRingMaxTasks>(x, off, msk, y, q, s);
 }
 
 int dispatch_ring_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
     switch (g_opt.fwd_threads) {
-    case 768: return launch_ring_fwd_tasks<12>(x, off, msk, y, q, s);
-    case 256: return launch_ring_fwd_tasks<4>(x, off, msk, y, q, s);
-    default: return launch_ring_fwd_tasks<8>(x, off, msk, y, q, s);
+    case 768: return launch_ring_fwd<12>(x, off, msk, y, q, s);
+    case 640: return launch_ring_fwd<10>(x, off, msk, y, q, s);
+    case 256: return launch_ring_fwd<4>(x, off, msk, y, q, s);
+    default: return launch_ring_fwd<8>(x, off, msk, y, q, s);
     }
 }
 
@@ -1395,7 +1385,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.lds_kb = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 64 || value == 128 || value == 256 || value == 512 || value == 768)) {
+    if (!strcmp(key, "fwd_threads") && (value == 0 || value == 64 || value == 128 || value == 256 || value == 512 || value == 640 || value == 768)) {
         g_opt.fwd_threads = value;
         return DCNV4_OK;
     }
