@@ -210,6 +210,13 @@ __device__ __forceinline__ int cvt_floor_i32(float v)
     return r;
 }
 
+__device__ __forceinline__ int cvt_round_i32(float v)      // floor(v + 0.5), saturating
+{
+    int r;
+    asm("v_cvt_rpi_i32_f32 %0, %1" : "=v"(r) : "v"(v));
+    return r;
+}
+
 __device__ __forceinline__ int med3i(int v, int lo, int hi)     // clamp to [lo, hi] in one instruction
 {
     int r;
@@ -1397,13 +1404,6 @@ const char *dcnv4_last_kernel_name(int backward)
     const char *n = g_last_kernel[backward ? 1 : 0];
     return n[0] ? n : nullptr;
 }
-
-#ifdef DCNV4_TRACE
-int dcnv4_debug_read_trace(void *dst, size_t bytes)
-{
-    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_dcnv4_trace), bytes < sizeof(g_dcnv4_trace) ? bytes : sizeof(g_dcnv4_trace));
-}
-#endif
 
 const char *dcnv4_status_string(int status)
 {
