@@ -499,18 +499,21 @@ __global__ __launch_bounds__(kThreads) void dcnv4_zero_kernel(u32x4 *__restrict_
 // ------------------------------------------------------------------------------------------
 namespace {
 
+// Test and benchmark switches (dcnv4_set_option): they force a path or a tile shape so that every
+// kernel can be checked on every shape; 0 = the library's own choice.  Not meant for applications.
 struct Options {
-    int fwd_cpt = 0, bwd_cpt = 0, xcd_remap = 1;
-    int fwd_path = 0;      // 0 auto, 1 direct global gather, 2 LDS-tiled
-    int halo = 0;          // 0 = default
-    int lds_kb = 0;        // LDS budget per workgroup of the tiled kernel, 0 = default
-    int fwd_threads = 0;   // 256 or 512 for the tiled kernel, 0 = default
-    int bwd_path = 0;      // 0 auto, 1 direct (global atomics), 2 LDS-tiled
+    int fwd_path = 0;      // 1 direct global gather, 2 rectangle staged in LDS, 3 ring of record rows in LDS
+    int bwd_path = 0;      // 1 direct (global atomics), 2 LDS-staged (two passes)
+    int fwd_cpt = 0;       // channels per lane of the direct forward (8 or 16)
+    int bwd_cpt = 0;       // channels per lane of the direct backward (1, 2, 4, 8, 16)
+    int xcd_remap = 1;     // consecutive tiles go to one XCD (0: plain block order)
+    int halo = 0;          // displacement in pixels (rows, for the ring) the staged window allows for
+    int lds_kb = 0;        // LDS budget per workgroup of the staged kernels (8..160)
+    int fwd_threads = 0;   // workgroup size of the staged forward kernels (64, 128, 256, 512, 640, 768)
+    int wg_per_cu = 0;     // persistent workgroups per compute unit of the rectangle kernels (1..16)
+    int fwd_single = 0;    // rectangle buffers of the staged gather kernels: 1 always two, 2 always one
+    int gx_threads = 0;    // workgroup size of the grad_x kernel (256, 512, 768)
     int gom_coop = 0;      // 1: the fp32 grad_offset/grad_mask pass goes through LDS slices even for whole groups
-    int batch_order = 0;   // 0 default (blocked in grad_x, interleaved elsewhere), 1 interleaved, 2 blocked
-    int wg_per_cu = 0;     // persistent workgroups per compute unit (1..4), 0 = default
-    int fwd_single = 0;    // rectangle buffers of the staged gather kernels: 0 auto, 1 always two, 2 always one
-    int gx_threads = 0;    // workgroup size of the grad_x kernel (256 or 512), 0 = default
 } g_opt;
 
 char g_last_kernel[2][96];
@@ -605,18 +608,16 @@ int make_geo(const Problem &q, int tpg, Geo *out)
 
 unsigned grid_of(const Geo &p) { return (unsigned)(p.remap ? p.tiles_per_xcd * kXcds : p.ntiles); }
 
-int default_fwd_cpt(int dtype, int Cg)
-{
-    (void)dtype;
-    return Cg == 8 ? 8 : 8;      // 16-byte (fp16) or 32-byte (fp32) runs per lane: neighbouring lanes share cache lines
-}
+// Eight channels per lane in the direct forward: 16-byte (fp16) or 32-byte (fp32) runs, so that
+// neighbouring lanes share cache lines.
+constexpr int kDefaultFwdCpt = 8;
 // One or two channels per lane: a wave's atomic instruction then covers a few whole cache lines
 // (16 lanes x 4 or 8 bytes per pixel) instead of 64 different ones, and the L2 atomic rate follows.
 int default_bwd_cpt(int Cg) { return Cg <= 32 ? 1 : Cg / 32; }
 
-int pick_fwd_cpt(int dtype, int Cg)
+int pick_fwd_cpt(int Cg)
 {
-    int c = g_opt.fwd_cpt ? g_opt.fwd_cpt : default_fwd_cpt(dtype, Cg);
+    int c = g_opt.fwd_cpt ? g_opt.fwd_cpt : kDefaultFwdCpt;
     if (c > Cg) c = Cg;
     if (Cg / c > 8) c = Cg / 8;        // at most 8 lanes per group
     return c;
@@ -668,18 +669,46 @@ constexpr int kMaxLdsBytes = 160 * 1024;
 // number of rows fits the LDS budget, otherwise split the columns too.  Returns false when
 // no tile with at least as many output rows/cols as the halo fits (the rectangle would be
 // mostly halo); the caller then uses the direct kernel.
+// Per-device caches (compute-unit count, dynamic-LDS grants) are indexed by the HIP device number.
+constexpr int kMaxDevices = 64;
+int current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return -1;
+    return dev;
+}
+
 // Number of compute units of the current device (persistent kernels launch one workgroup each).
 int device_cus()
 {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
+    static int cus[kMaxDevices];
+    const int dev = current_device();
+    if (dev < 0)
+        return 0;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
             return 0;
-        cus = n;
+        cus[dev] = n;
     }
-    return cus;
+    return cus[dev];
+}
+
+// Lets `kern` use `lds` bytes of dynamic LDS on the current device (asked for once per device and size).
+bool grant_lds(const void *kern, int lds, int (&granted)[kMaxDevices])
+{
+    if (lds <= 64 * 1024)
+        return true;
+    const int dev = current_device();
+    if (dev < 0)
+        return false;
+    if (lds > granted[dev]) {
+        if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return false;
+        granted[dev] = lds;
+    }
+    return true;
 }
 
 bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, bool with_slices,
@@ -811,7 +840,7 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
     p.nblocks = (int)nblocks;
     p.blocks_per_xcd = (int)((nblocks + kXcds - 1) / kXcds);
     p.remap = g_opt.xcd_remap;
-    p.blocked = g_opt.batch_order ? g_opt.batch_order == 2 : gradx;
+    p.blocked = gradx;
     p.div_g = make_div((unsigned)q.G);
     p.div_s = make_div((unsigned)chan_slices);
     p.slices = chan_slices;
@@ -830,11 +859,17 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
     return DCNV4_OK;
 }
 
-// Launch of the LDS-staged kernel in one of its modes; `which` = 0 forward, 1 backward (for the
-// kernel-name record).
+// A launch of the LDS-staged kernel in one of its modes, in two steps: prepare_tiled does everything
+// that can refuse (tile choice, LDS size, LDS grant, device query) and launches nothing; run_tiled
+// launches what was prepared.  `which` = 0 forward, 1 backward (for the kernel-name record).
+struct TiledLaunch {
+    TGeo p;
+    int lds;
+    unsigned grid;
+};
+
 template <typename T, int CG, int THREADS, int MODE>
-int launch_tiled(const void *x, const void *off, const void *msk, const void *gy, void *o1, void *o2,
-                 const Problem &q, hipStream_t s, int which, bool any_tile_size, int want_nbuf = 0, int want_per_cu = 0)
+int prepare_tiled(const Problem &q, bool any_tile_size, int want_nbuf, int want_per_cu, TiledLaunch *out)
 {
     TGeo p;
     constexpr bool kGradX = MODE == kTiledGradX;
@@ -851,14 +886,9 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
     const int lds = p.nbuf * p.xtile_bytes + slices + tail;
     if (lds > kMaxLdsBytes)
         return DCNV4_ERR_UNSUPPORTED;
-    auto kern = dcnv4_tiled_kernel<T, CG, THREADS, MODE>;
-    static int granted = 0;                  // largest dynamic-LDS size already requested for this kernel
-    if (lds > 64 * 1024 && lds > granted) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lds) != hipSuccess)
-            return DCNV4_ERR_LAUNCH;
-        granted = lds;
-    }
+    static int granted[kMaxDevices];         // largest dynamic-LDS size already requested for this kernel, per device
+    if (!grant_lds(reinterpret_cast<const void *>(dcnv4_tiled_kernel<T, CG, THREADS, MODE>), lds, granted))
+        return DCNV4_ERR_LAUNCH;
     // persistent workgroups: one per compute unit (or fewer when there are fewer tiles)
     const int cus = device_cus();
     if (cus <= 0)
@@ -876,11 +906,32 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
     } else {
         grid = (unsigned)(slots < p.nblocks ? slots : p.nblocks);
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds, s, (const T *)x, (const T *)off, (const T *)msk,
-                       (const T *)gy, (T *)o1, (T *)o2, p);
+    out->p = p;
+    out->lds = lds;
+    out->grid = grid;
+    return DCNV4_OK;
+}
+
+template <typename T, int CG, int THREADS, int MODE>
+int run_tiled(const TiledLaunch &l, const void *x, const void *off, const void *msk, const void *gy, void *o1, void *o2,
+              hipStream_t s, int which)
+{
+    hipLaunchKernelGGL((dcnv4_tiled_kernel<T, CG, THREADS, MODE>), dim3(l.grid), dim3(THREADS), l.lds, s, (const T *)x,
+                       (const T *)off, (const T *)msk, (const T *)gy, (T *)o1, (T *)o2, l.p);
     snprintf(g_last_kernel[which], sizeof(g_last_kernel[which]), "dcnv4_tiled_kernel<%s, %d, %d, %d>",
              sizeof(T) == 2 ? "_Float16" : "float", CG, THREADS, MODE);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
+template <typename T, int CG, int THREADS, int MODE>
+int launch_tiled(const void *x, const void *off, const void *msk, const void *gy, void *o1, void *o2,
+                 const Problem &q, hipStream_t s, int which, bool any_tile_size, int want_nbuf = 0, int want_per_cu = 0)
+{
+    TiledLaunch l;
+    const int rc = prepare_tiled<T, CG, THREADS, MODE>(q, any_tile_size, want_nbuf, want_per_cu, &l);
+    if (rc)
+        return rc;
+    return run_tiled<T, CG, THREADS, MODE>(l, x, off, msk, gy, o1, o2, s, which);
 }
 
 template <typename T, int CG, int THREADS>
@@ -1083,13 +1134,9 @@ int launch_ring_fwd(const void *x, const void *off, const void *msk, void *y, co
     if (lds > kMaxLdsBytes)
         return DCNV4_ERR_UNSUPPORTED;
     auto kern = dcnv4_ring_fwd_kernel<WAVES>;
-    static int granted = 0;
-    if (lds > 64 * 1024 && lds > granted) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lds) != hipSuccess)
-            return DCNV4_ERR_LAUNCH;
-        granted = lds;
-    }
+    static int granted[kMaxDevices];
+    if (!grant_lds(reinterpret_cast<const void *>(kern), lds, granted))
+        return DCNV4_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), lds, s, (const _Float16 *)x, (const _Float16 *)off,
                        (const _Float16 *)msk, (_Float16 *)y, p);
     snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_ring_fwd_kernel<%d>", WAVES);
@@ -1121,7 +1168,7 @@ int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 2)
             return rc;
     }
-    const int cpt = pick_fwd_cpt(q.dtype, q.Cg);
+    const int cpt = pick_fwd_cpt(q.Cg);
     switch (q.Cg) {
     case 8: return dispatch_fwd_cpt<T, 8>(cpt, x, off, msk, y, q, s);
     case 16: return dispatch_fwd_cpt<T, 16>(cpt, x, off, msk, y, q, s);
@@ -1172,7 +1219,8 @@ int dispatch_bwd_cpt(int cpt, const void *x, const void *off, const void *msk, c
 
 // Backward through the LDS-staged kernels: zero-fill of grad_x, then the grad_offset/grad_mask
 // pass (gathers, like the forward) and the grad_x pass (LDS-private accumulation, one flush per
-// tile).  Both are validated before anything is launched, so an unsupported shape writes nothing.
+// tile).  Both passes are prepared -- everything that can refuse -- before anything is launched,
+// so a call that returns an error has written nothing.
 template <typename T, int CG>
 int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void *gy, void *gx, void *go, void *gm,
                      const Problem &q, hipStream_t s)
@@ -1182,46 +1230,50 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     // CG is the kernels' channel run; a wider group (q.Cg) goes through as q.Cg / CG slices whose
     // grad_offset/grad_mask parts are added up in zero-filled outputs
     const bool sliced = q.Cg != CG;
-    TGeo probe;
-    const bool gom_direct = sizeof(T) == 4 && !sliced && g_opt.gom_coop == 0;
-    int rc = make_tgeo(q, gom_direct ? 512 : THREADS, gom_direct ? kTiledGradOMDirect : kTiledGradOM, &probe, CG);
-    if (rc)
-        return rc;
+    // whole fp32 groups: the lanes read and write their own pixels' values, no LDS slices, eight waves
+    bool gom_direct = false;
+    if constexpr (sizeof(T) == 4)
+        gom_direct = !sliced && g_opt.gom_coop == 0;
     // (for fp16 there is no other backward, so the tile-size heuristic does not apply)
     const bool any_size = g_opt.bwd_path == 2 || sizeof(T) == 2;
-    if (!any_size && probe.R * probe.Q < 128)
-        return DCNV4_ERR_UNSUPPORTED;
-    // the grad_x pass is a chain of LDS round trips per lane: twelve waves hide them best (measured)
+    // the grad_x pass: twelve waves keep the LDS busiest (measured)
     const int gxt = g_opt.gx_threads ? g_opt.gx_threads : 768;
-    rc = make_tgeo(q, gxt, kTiledGradX, &probe, CG);
+    TiledLaunch l_gom, l_gx;
+    int rc;
+    if constexpr (sizeof(T) == 4) {
+        rc = gom_direct ? prepare_tiled<T, CG, 512, kTiledGradOMDirect>(q, any_size, 0, 0, &l_gom)
+                        : prepare_tiled<T, CG, THREADS, kTiledGradOM>(q, any_size, 0, 0, &l_gom);
+    } else {
+        rc = prepare_tiled<T, CG, THREADS, kTiledGradOM>(q, any_size, 0, 0, &l_gom);
+    }
     if (rc)
         return rc;
-    if (!any_size && probe.R * probe.Q < 128)
-        return DCNV4_ERR_UNSUPPORTED;
+    rc = gxt == 768   ? prepare_tiled<T, CG, 768, kTiledGradX>(q, any_size, 0, 0, &l_gx)
+         : gxt == 512 ? prepare_tiled<T, CG, 512, kTiledGradX>(q, any_size, 0, 0, &l_gx)
+                      : prepare_tiled<T, CG, 256, kTiledGradX>(q, any_size, 0, 0, &l_gx);
+    if (rc)
+        return rc;
     auto zero = [&](void *ptr, long long bytes) {
         long long zb = (bytes / 16 + kThreads - 1) / kThreads;
         if (zb > 8192) zb = 8192;
         if (zb < 1) zb = 1;
         hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)ptr, bytes);
     };
-    zero(gx, (long long)q.N * probe.x_img_bytes);
+    zero(gx, (long long)q.N * l_gx.p.x_img_bytes);
     if (sliced) {
-        zero(go, (long long)q.N * probe.off_img_bytes);
-        zero(gm, (long long)q.N * probe.msk_img_bytes);
+        zero(go, (long long)q.N * l_gom.p.off_img_bytes);
+        zero(gm, (long long)q.N * l_gom.p.msk_img_bytes);
     }
     if constexpr (sizeof(T) == 4) {
-        // whole fp32 groups: the lanes read and write their own pixels' values, no LDS slices, eight waves
-        if (!sliced && g_opt.gom_coop == 0)
-            rc = launch_tiled<T, CG, 512, kTiledGradOMDirect>(x, off, msk, gy, go, gm, q, s, 1, true);
-        else
-            rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
+        rc = gom_direct ? run_tiled<T, CG, 512, kTiledGradOMDirect>(l_gom, x, off, msk, gy, go, gm, s, 1)
+                        : run_tiled<T, CG, THREADS, kTiledGradOM>(l_gom, x, off, msk, gy, go, gm, s, 1);
     } else {
-        rc = launch_tiled<T, CG, THREADS, kTiledGradOM>(x, off, msk, gy, go, gm, q, s, 1, true);
+        rc = run_tiled<T, CG, THREADS, kTiledGradOM>(l_gom, x, off, msk, gy, go, gm, s, 1);
     }
     if (rc == DCNV4_OK)
-        rc = gxt == 768   ? launch_tiled<T, CG, 768, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
-             : gxt == 512 ? launch_tiled<T, CG, 512, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true)
-                          : launch_tiled<T, CG, 256, kTiledGradX>(x, off, msk, gy, gx, nullptr, q, s, 1, true);
+        rc = gxt == 768   ? run_tiled<T, CG, 768, kTiledGradX>(l_gx, x, off, msk, gy, gx, nullptr, s, 1)
+             : gxt == 512 ? run_tiled<T, CG, 512, kTiledGradX>(l_gx, x, off, msk, gy, gx, nullptr, s, 1)
+                          : run_tiled<T, CG, 256, kTiledGradX>(l_gx, x, off, msk, gy, gx, nullptr, s, 1);
     return rc;
 }
 
@@ -1344,6 +1396,10 @@ int dcnv4_set_option(const char *key, int value)
 {
     if (!key)
         return DCNV4_ERR_NULL;
+    if (!strcmp(key, "reset")) {             // every switch back to the library's own choice
+        g_opt = Options();
+        return DCNV4_OK;
+    }
     if (!strcmp(key, "fwd_cpt") && (value == 0 || value == 8 || value == 16)) {
         g_opt.fwd_cpt = value;
         return DCNV4_OK;
@@ -1370,10 +1426,6 @@ int dcnv4_set_option(const char *key, int value)
     }
     if (!strcmp(key, "gom_coop") && (value == 0 || value == 1)) {
         g_opt.gom_coop = value;
-        return DCNV4_OK;
-    }
-    if (!strcmp(key, "batch_order") && value >= 0 && value <= 2) {
-        g_opt.batch_order = value;
         return DCNV4_OK;
     }
     if (!strcmp(key, "wg_per_cu") && value >= 0 && value <= 16) {

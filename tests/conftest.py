@@ -27,3 +27,16 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _library_switches_back_to_default():
+    """The library's test switches are process-wide: whatever a test sets (or leaves set when it
+    fails half-way) is undone before the next test starts."""
+    yield
+    try:
+        from paper_2401_06197_amd import binding
+        if os.path.exists(binding.LIB_PATH):
+            binding.dcnv4_set_option("reset", 0)
+    except Exception:
+        pass

@@ -110,6 +110,27 @@ def test_fp16_backward_geometries(cfg, opts):
 
 
 # ------------------------------------------------------------------ geometry / tiling coverage
+BIG_PAD = [Config("pad20", N=1, H=14, W=14, C=64, G=4, pad=20), Config("pad9_s2", N=2, H=10, W=12, C=32, G=2, pad=9, stride=2),
+           Config("pad20_cg8", N=1, H=14, W=14, C=32, G=4, pad=20)]
+
+
+@pytest.mark.parametrize("cfg", BIG_PAD, ids=[c.name for c in BIG_PAD])
+@pytest.mark.parametrize("opts", [{}, {"fwd_path": 2, "bwd_path": 2}, {"fwd_path": 2, "bwd_path": 2, "lds_kb": 40, "halo": 2},
+                                  {"fwd_path": 3}], ids=["default", "staged", "staged_small", "ring"])
+def test_padding_far_beyond_the_halo(cfg, opts):
+    """Output pixels whose whole window lies outside the image: their tiles stage nothing, every
+    result there is zero (Eq. 1 reads zero outside), and the backward adds nothing for them."""
+    for k, v in opts.items():
+        dcn.dcnv4_set_option(k, v)
+    for dtype in ("f32", "f16"):
+        if opts.get("fwd_path") == 3 and (dtype != "f16" or cfg.Cg != 16):
+            continue
+        check_forward(cfg, dtype, seed=21)
+    if opts.get("fwd_path") != 3:
+        check_backward(cfg, seed=22)
+        check_backward(cfg, seed=22, dtype="f16")
+
+
 SMALL = [
     # several tiles and a ragged tail per image (Ho*Wo*G not a multiple of the tile), N > 1
     Config("rag1", N=3, H=13, W=11, C=48, G=3),
