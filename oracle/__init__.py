@@ -22,7 +22,8 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # (the mutation check of the pins points this at a deliberately broken copy, built elsewhere)
+        path = os.environ.get("DCNV4_ORACLE_LIB") or _build.build(force=False)
         lib = ctypes.CDLL(path)
         dp = ctypes.POINTER(ctypes.c_double)
         ints = [ctypes.c_int] * 13
@@ -100,3 +101,32 @@ def backward(x, offset, mask, grad_y, kernel=3, stride=1, pad=1, dilation=1, off
     if rc:
         raise ValueError("dcnv4_oracle_backward: bad geometry")
     return gx, go, gm
+
+
+def split_merged(om, kernel=3):
+    """[N,Ho,Wo,G,32] buffer of Sec. 3.2 "Micro design" (the single linear layer's output per group:
+    2K offsets, K mask values, padding up to 32) -> (offset [N,Ho,Wo,G,K,2], mask [N,Ho,Wo,G,K])."""
+    kh, kw = _pair(kernel)
+    K = kh * kw
+    om = np.asarray(om)
+    if om.ndim != 5 or om.shape[4] < 3 * K:
+        raise ValueError(f"merged offset/mask buffer of shape {om.shape}: last dimension must hold {3 * K} values")
+    offset = om[..., :2 * K].reshape(om.shape[:4] + (K, 2))
+    mask = om[..., 2 * K:3 * K]
+    return offset, mask
+
+
+def forward_merged(x, om, **kw):
+    offset, mask = split_merged(om, kw.get("kernel", 3))
+    return forward(x, offset, mask, **kw)
+
+
+def backward_merged(x, om, grad_y, **kw):
+    """Returns (grad_x, grad_om) with grad_om laid out like om; its padding entries are zero."""
+    offset, mask = split_merged(om, kw.get("kernel", 3))
+    gx, go, gm = backward(x, offset, mask, grad_y, **kw)
+    K = mask.shape[4]
+    gom = np.zeros(np.asarray(om).shape, dtype=np.float64)
+    gom[..., :2 * K] = go.reshape(go.shape[:4] + (2 * K,))
+    gom[..., 2 * K:3 * K] = gm
+    return gx, gom
