@@ -30,6 +30,10 @@ def parse():
     ap.add_argument("--sets", type=int, default=4, help="buffer sets rotated per leg")
     ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16")
     ap.add_argument("--workload", default="c2")
+    ap.add_argument("--more-workloads", default="c3_28,c3_14,c3_7,c4",
+                    help="further workloads whose fp16 forward is timed and reported under legs as fwd_f16@<name>")
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="also time the forward (fp32 and fp16) at the ten shapes of the paper's Tab. 2 and 3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--cold-only", action="store_true", help="skip the back-to-back (hot) timing loop")
@@ -49,17 +53,45 @@ def ensure_built():
     return binding
 
 
-def measured_traffic(leg, workload):
+def measured_traffic(leg, workload, kernel=None):
     """HBM bytes per launch of the leg's kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    (scaled by a copy of known size); read from the committed profile summary, None if there is none."""
+    (scaled by a copy of known size); read from the committed profile summary.  None if there is no
+    summary, or if it was taken on another kernel than the one that ran now (`kernel`)."""
     path = os.path.join(ROOT, "profiles", f"{leg}_{workload}_hbm_traffic.md")
+    traffic, profiled = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return int(line.split("=")[1].split()[0])
+                traffic = int(line.split("=")[1].split()[0])
+            if line.startswith("kernel"):
+                profiled = line.split("=", 1)[1].strip().strip("`")
     except OSError:
-        pass
-    return None
+        return None
+    if kernel is not None and profiled != kernel:
+        return None
+    return traffic
+
+
+def copy_ceiling(torch, stream, nbytes, steps):
+    """GB/s (bytes read + bytes written) of a plain device-to-device copy of nbytes/2 bytes, i.e. of the
+    same total traffic as the headline kernel's algorithmic bytes: what this machine's memory system gives
+    a kernel that does nothing but stream."""
+    half = max(1 << 20, (nbytes // 2) & ~255)
+    srcs = [torch.empty(half, dtype=torch.uint8, device="cuda:0").fill_(i + 1) for i in range(4)]
+    dsts = [torch.empty_like(t) for t in srcs]
+    with torch.cuda.stream(stream):
+        for i in range(8):
+            dsts[i % 4].copy_(srcs[i % 4])
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        stream.synchronize()
+        start.record(stream)
+        for i in range(steps):
+            dsts[i % 4].copy_(srcs[i % 4])
+        stop.record(stream)
+        stop.synchronize()
+    us = start.elapsed_time(stop) / steps * 1e3
+    return {"bytes_moved": 2 * half, "us_per_copy": round(us, 3), "GBps": 2 * half / (us * 1e-6) / 1e9,
+            "frac_of_hbm_peak": 2 * half / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
 
 def time_leg(torch, stream, launch, nsets, steps, warmup, cold_only=False):
@@ -84,6 +116,69 @@ def time_leg(torch, stream, launch, nsets, steps, warmup, cold_only=False):
     return out
 
 
+def run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_output=False):
+    """Times one leg ("fwd_f16", "bwd_f32", ...) on workload cfg; returns (record, first output or None)."""
+    from paper_2401_06197_amd.synth import make_inputs
+    dev = torch.device("cuda:0")
+    Ho, Wo = cfg.out_hw
+    out_elems = cfg.N * Ho * Wo * cfg.C
+    geo = dict(kernel=cfg.kernel, stride=cfg.stride, pad=cfg.pad, dilation=cfg.dilation, offset_scale=cfg.offset_scale)
+    direction, dt = leg.split("_")
+    tdt = {"f16": torch.float16, "f32": torch.float32}[dt]
+    code = {"f16": dcn.DCNV4_F16, "f32": dcn.DCNV4_F32}[dt]
+    if (cfg.name, dt) not in host_inputs:
+        host_inputs[(cfg.name, dt)] = make_inputs(cfg, dt, seed=0)
+    base = {k: torch.from_numpy(v).to(dev) for k, v in host_inputs[(cfg.name, dt)].items()}
+    # enough buffer sets that a launch does not find its inputs in the 256 MB memory-side cache
+    one_set = sum(v.numel() * v.element_size() for v in base.values())
+    nsets = max(a.sets, min(16, -(-(320 << 20) // one_set)))
+    sets = [base] + [{k: v.clone() for k, v in base.items()} for _ in range(nsets - 1)]
+    if direction == "fwd":
+        outs = [torch.empty((cfg.N, Ho, Wo, cfg.C), dtype=tdt, device=dev) for _ in range(nsets)]
+        alg = dcn.dcnv4_forward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
+        argv = [dcn.dcnv4_forward(s["x"], s["offset"], s["mask"], out=o, stream=stream, prepare_only=True, **geo)
+                for s, o in zip(sets, outs)]
+        fn = lib.dcnv4_forward
+    else:
+        outs = [(torch.empty_like(s["x"]), torch.empty_like(s["offset"]), torch.empty_like(s["mask"])) for s in sets]
+        alg = dcn.dcnv4_backward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
+        argv = [dcn.dcnv4_backward(s["x"], s["offset"], s["mask"], s["grad_y"], out=o, stream=stream,
+                                   prepare_only=True, **geo) for s, o in zip(sets, outs)]
+        fn = lib.dcnv4_backward
+
+    def launch(i):
+        rc = fn(*argv[i])
+        if rc:
+            raise dcn.Dcnv4Error(rc, leg)
+    torch.cuda.synchronize()
+    t = time_leg(torch, stream, launch, nsets, steps, a.warmup, a.cold_only)
+    rec = {
+        "workload": cfg.name,
+        "kernel": dcn.dcnv4_last_kernel_name(direction == "bwd"),
+        "steps": steps,
+        "us_per_launch": round(t["cold"] * 1e3, 3),
+        "out_elems_per_s": out_elems / (t["cold"] * 1e-3),
+        "algorithmic_bytes": alg,
+        "GBps": alg / (t["cold"] * 1e-3) / 1e9,
+        "frac_of_hbm_peak": alg / (t["cold"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "hot_us_per_launch": None if a.cold_only else round(t["hot"] * 1e3, 3),
+        "hot_GBps": None if a.cold_only else alg / (t["hot"] * 1e-3) / 1e9,
+        "buffer_sets": nsets,
+    }
+    rec["traffic"] = measured_traffic(leg, cfg.name, rec["kernel"])
+    y = outs[0].float().cpu().numpy() if (keep_output and direction == "fwd") else None
+    del sets, outs, base
+    torch.cuda.empty_cache()
+    return rec, y
+
+
+# the paper's op-level numbers (Tab. 2 and 3, A100 80GB SXM, microseconds, fp32 / fp16): context, not a target
+PAPER_A100_US = {"paper_56x56x128": (606, 404), "paper_28x28x256": (303, 230), "paper_14x14x512": (145, 123),
+                 "paper_7x7x1024": (73.0, 68.0), "paper_14x14x768": (224, 147), "paper_200x320x128": (210, 136),
+                 "paper_100x160x256": (124, 89.5), "paper_50x80x512": (70.7, 58.9), "paper_25x40x1024": (45.2, 42.6),
+                 "paper_64x64x768": (103, 67.2)}
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -97,7 +192,7 @@ def main():
     for kv in a.opt:
         k, v = kv.split("=")
         dcn.dcnv4_set_option(k, int(v))
-    from paper_2401_06197_amd.synth import CONFIGS, make_inputs
+    from paper_2401_06197_amd.synth import CONFIGS
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -117,56 +212,27 @@ def main():
     legs_wanted = [s for s in a.legs.split(",") if s]
     legs = {}
     host_inputs = {}
-
+    head_y = None
     for leg in legs_wanted:
-        direction, dt = leg.split("_")
-        tdt = {"f16": torch.float16, "f32": torch.float32}[dt]
-        code = {"f16": dcn.DCNV4_F16, "f32": dcn.DCNV4_F32}[dt]
-        if dt not in host_inputs:
-            host_inputs[dt] = make_inputs(cfg, dt, seed=0)
-        base = {k: torch.from_numpy(v).to(dev) for k, v in host_inputs[dt].items()}
-        sets = [base] + [{k: v.clone() for k, v in base.items()} for _ in range(a.sets - 1)]
-        if direction == "fwd":
-            outs = [torch.empty((cfg.N, Ho, Wo, cfg.C), dtype=tdt, device=dev) for _ in range(a.sets)]
-            alg = dcn.dcnv4_forward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
-
-            argv = [dcn.dcnv4_forward(s["x"], s["offset"], s["mask"], out=o, stream=stream, prepare_only=True, **geo)
-                    for s, o in zip(sets, outs)]
-            fn = lib.dcnv4_forward
-        else:
-            outs = [(torch.empty_like(s["x"]), torch.empty_like(s["offset"]), torch.empty_like(s["mask"])) for s in sets]
-            alg = dcn.dcnv4_backward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
-
-            argv = [dcn.dcnv4_backward(s["x"], s["offset"], s["mask"], s["grad_y"], out=o, stream=stream,
-                                       prepare_only=True, **geo) for s, o in zip(sets, outs)]
-            fn = lib.dcnv4_backward
-
-        def launch(i, fn=fn, argv=argv):
-            rc = fn(*argv[i])
-            if rc:
-                raise dcn.Dcnv4Error(rc, leg)
-        torch.cuda.synchronize()
-        steps = a.steps if direction == "fwd" else max(1, a.steps // 4)
-        t = time_leg(torch, stream, launch, a.sets, steps, a.warmup, a.cold_only)
-        legs[leg] = {
-            "kernel": dcn.dcnv4_last_kernel_name(direction == "bwd"),
-            "steps": steps,
-            "us_per_launch": round(t["cold"] * 1e3, 3),
-            "out_elems_per_s": out_elems / (t["cold"] * 1e-3),
-            "algorithmic_bytes": alg,
-            "GBps": alg / (t["cold"] * 1e-3) / 1e9,
-            "frac_of_hbm_peak": alg / (t["cold"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "hot_us_per_launch": None if a.cold_only else round(t["hot"] * 1e3, 3),
-            "hot_GBps": None if a.cold_only else alg / (t["hot"] * 1e-3) / 1e9,
-            "buffer_sets": a.sets,
-        }
+        steps = a.steps if leg.startswith("fwd") else max(1, a.steps // 4)
+        legs[leg], y = run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_output=leg == legs_wanted[0])
         if leg == legs_wanted[0]:
-            head_y = outs[0].float().cpu().numpy() if direction == "fwd" else None
-        del sets, outs, base
-        torch.cuda.empty_cache()
-
+            head_y = y
     head = legs_wanted[0]
     hl = legs[head]
+    head_inputs = host_inputs[(cfg.name, head.split("_")[1])]
+    host_inputs = {k: v for k, v in host_inputs.items() if k == (cfg.name, head.split("_")[1])}
+
+    # the other workloads (fp16 forward), and on request the paper's own benchmark shapes
+    for name in [w for w in a.more_workloads.split(",") if w and w != cfg.name]:
+        legs[f"fwd_f16@{name}"], _ = run_leg(torch, dcn, lib, stream, CONFIGS[name], "fwd_f16", a, {}, a.steps)
+    if a.paper_shapes:
+        for name, (us32, us16) in PAPER_A100_US.items():
+            for leg, ref_us in (("fwd_f32", us32), ("fwd_f16", us16)):
+                r, _ = run_leg(torch, dcn, lib, stream, CONFIGS[name], leg, a, {}, a.steps)
+                r["paper_a100_us"] = ref_us
+                legs[f"{leg}@{name}"] = r
+
     rec = {
         "metric": "DCNv4 fwd/bwd output elems/s and achieved HBM GB/s (% of peak) at 56x56x128",
         "value": hl["out_elems_per_s"],
@@ -183,13 +249,15 @@ def main():
         "config": {"workload": f"{cfg.name}: N={cfg.N} {cfg.H}x{cfg.W} C={cfg.C} G={cfg.G} 3x3 s1 p1, leg {head}",
                    "offset_std_px": cfg.sigma, "cache": "cold (rotating buffer sets)"},
         "roofline": {"bound": "hbm", "kernel": hl["kernel"], "achieved": hl["GBps"], "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": hl["frac_of_hbm_peak"], "traffic": measured_traffic(head, cfg.name)},
+                     "unit": "GB/s", "frac": hl["frac_of_hbm_peak"], "traffic": hl["traffic"]},
+        "copy_ceiling": copy_ceiling(torch, stream, hl["algorithmic_bytes"], max(20, a.steps // 4)),
         "legs": legs,
     }
 
     if not a.no_cpu_baseline:
+        import ctypes
         import oracle
-        t = host_inputs[head.split("_")[1]]
+        t = head_inputs
         reps, spent, ref = 0, 0.0, None
         while spent < a.cpu_seconds and reps < 40:
             t0 = time.perf_counter()
@@ -200,10 +268,30 @@ def main():
             "value": out_elems * reps / spent, "unit": "output elems/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"{reps} full forward passes of the same workload (double precision, {spent:.1f} s)",
         }
+        # the same oracle on one host thread, on the first images of the batch (a bounded sample)
+        try:
+            omp = ctypes.CDLL("libgomp.so.1")
+            many = oracle.threads()
+            n1 = max(1, cfg.N // 16)
+            omp.omp_set_num_threads(1)
+            t0 = time.perf_counter()
+            oracle.forward(t["x"][:n1], t["offset"][:n1], t["mask"][:n1], **geo)
+            dt1 = time.perf_counter() - t0
+            omp.omp_set_num_threads(many)
+            rec["cpu_baseline"]["single_thread"] = {
+                "value": (out_elems // cfg.N) * n1 / dt1, "unit": "output elems/s", "cores": 1,
+                "sample": f"one forward pass over the first {n1} of {cfg.N} images ({dt1:.1f} s)"}
+        except OSError:
+            pass
         if head_y is not None:
             err = np.abs(head_y - ref)
             tol = 2e-2 if head.endswith("f16") else 1e-5
-            rec["parity"] = {"max_abs_err": float(err.max()), "within_tol": bool(np.all(err <= tol + tol * np.abs(ref)))}
+            big = np.abs(ref) >= 1.0
+            rec["parity"] = {"max_abs_err": float(err.max()),
+                             "max_rel_err": float((err[big] / np.abs(ref[big])).max()) if big.any() else None,
+                             "max_rel_err_note": "over outputs with |reference| >= 1",
+                             "max_err_over_tolerance": float((err / (tol + tol * np.abs(ref))).max()),
+                             "within_tol": bool(np.all(err <= tol + tol * np.abs(ref)))}
     print(json.dumps(rec))
 
 

@@ -1145,18 +1145,18 @@ int launch_ring_fwd(const void *x, const void *off, const void *msk, void *y, co
 
 int dispatch_ring_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
-    switch (g_opt.fwd_threads) {
-    case 768: return launch_ring_fwd<12>(x, off, msk, y, q, s);
-    case 640: return launch_ring_fwd<10>(x, off, msk, y, q, s);
-    case 256: return launch_ring_fwd<4>(x, off, msk, y, q, s);
-    default: return launch_ring_fwd<8>(x, off, msk, y, q, s);
-    }
+    // eight waves: two per SIMD, 256 registers each (four waves on request, for tests)
+    if (g_opt.fwd_threads == 256)
+        return launch_ring_fwd<4>(x, off, msk, y, q, s);
+    return launch_ring_fwd<8>(x, off, msk, y, q, s);
 }
 
 template <typename T>
 int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
-    if (sizeof(T) == 2 && (g_opt.fwd_path == 0 || g_opt.fwd_path == 3)) {
+    // (maps of a few batches per image leave most of a ring workgroup idle: the rectangle kernels,
+    // with several small workgroups per compute unit, are faster there -- measured at 14x14 and 7x7)
+    if (sizeof(T) == 2 && (g_opt.fwd_path == 3 || (g_opt.fwd_path == 0 && q.Ho * q.Wo >= 512))) {
         const int rc = dispatch_ring_fwd(x, off, msk, y, q, s);
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 3)
             return rc;
@@ -1225,8 +1225,9 @@ template <typename T, int CG>
 int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void *gy, void *gx, void *go, void *gm,
                      const Problem &q, hipStream_t s)
 {
-    // the gather pass keeps 4*Cg inputs and gy per lane: eight waves fit the register file in fp16, four in fp32
-    constexpr int THREADS = sizeof(T) == 2 ? 512 : 256;
+    // the gather pass keeps 4*Cg inputs and gy per lane: eight waves fit the register file with pixels of up to
+    // 32 bytes, four with 64-byte pixels
+    constexpr int THREADS = CG * sizeof(T) >= 64 ? 256 : 512;
     // CG is the kernels' channel run; a wider group (q.Cg) goes through as q.Cg / CG slices whose
     // grad_offset/grad_mask parts are added up in zero-filled outputs
     const bool sliced = q.Cg != CG;
@@ -1357,6 +1358,8 @@ int dcnv4_backward(const void *x, const void *offset, const void *mask, const vo
             return launch_bwd_tiled<_Float16, 8>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         if (Cg == 16)
             return launch_bwd_tiled<_Float16, 16>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+        if (Cg == 32)                                  // 64-byte pixels, like fp32 groups of 16
+            return launch_bwd_tiled<_Float16, 32>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         return DCNV4_ERR_UNSUPPORTED;
     }
     if (g_opt.bwd_path != 1) {

@@ -18,3 +18,5 @@ def test_traffic_figure_comes_from_the_committed_profile():
     t = bench.measured_traffic("fwd_f16", "c2")
     assert t is not None and 0.9 < t / 189_464_576 < 1.5
     assert bench.measured_traffic("fwd_f16", "no_such_workload") is None
+    # ... and only for the kernel it was measured on
+    assert bench.measured_traffic("fwd_f16", "c2", kernel="some_other_kernel<1>") is None

@@ -91,6 +91,35 @@ def test_c5_shape_backward_fp16():
     check_backward(CONFIGS["c1"], dtype="f16")
 
 
+# ------------------------------------------------------------------ the paper's own benchmark shapes
+PAPER_SHAPES = [n for n in CONFIGS if n.startswith("paper_")]
+
+
+@pytest.mark.parametrize("name", PAPER_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_paper_benchmark_shapes_forward_full_size(name, dtype):
+    """The ten shapes of Tab. 2 and 3 (32 channels per group), full size, every output element."""
+    check_forward(CONFIGS[name], dtype)
+
+
+@pytest.mark.parametrize("name", ["paper_56x56x128", "paper_14x14x768", "paper_100x160x256", "paper_25x40x1024"])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_paper_benchmark_shapes_backward_full_size(name, dtype):
+    check_backward(CONFIGS[name], dtype=dtype)
+
+
+FP16_BWD32 = [Config("hb32a", N=2, H=13, W=11, C=64, G=2), Config("hb32b", N=1, H=20, W=33, C=96, G=3, sigma=3.0),
+              Config("hb32s2", N=2, H=17, W=15, C=32, G=1, stride=2, pad=2, dilation=2)]
+
+
+@pytest.mark.parametrize("cfg", FP16_BWD32, ids=[c.name for c in FP16_BWD32])
+@pytest.mark.parametrize("opts", [{}, {"halo": 1}, {"gx_threads": 256, "lds_kb": 64}], ids=["default", "halo1", "gx256"])
+def test_fp16_backward_groups_of_32(cfg, opts):
+    for k, v in opts.items():
+        dcn.dcnv4_set_option(k, v)
+    check_backward(cfg, seed=31, dtype="f16")
+
+
 FP16_BWD = [Config("hb1", N=3, H=20, W=23, C=64, G=4), Config("hb8", N=2, H=11, W=10, C=16, G=2),
             Config("hbs2", N=2, H=21, W=17, C=32, G=2, stride=2, pad=2, dilation=2, sigma=3.0),
             Config("hbwide", N=1, H=9, W=70, C=48, G=3, sigma=5.0), Config("hbrow", N=1, H=1, W=37, C=32, G=2)]
@@ -320,8 +349,8 @@ def test_gpu_call_with_bad_arguments_returns_error_and_writes_nothing():
                           kernel=5, out=y[:, :6, :6].contiguous())
     assert e.value.status == 3
     with pytest.raises(dcn.Dcnv4Error):
-        wide = to_gpu(make_inputs(Config("wide", N=1, H=8, W=8, C=64, G=2), "f16", seed=11), "f16")
-        dcn.dcnv4_backward(wide["x"], wide["offset"], wide["mask"], wide["grad_y"])   # fp16 backward: Cg 8 or 16 only
+        wide = to_gpu(make_inputs(Config("wide", N=1, H=8, W=8, C=128, G=2), "f16", seed=11), "f16")
+        dcn.dcnv4_backward(wide["x"], wide["offset"], wide["mask"], wide["grad_y"])   # fp16 backward: Cg 8, 16 or 32 only
     torch.cuda.synchronize()
     assert torch.all(y == 5.0)
 
@@ -408,9 +437,11 @@ def test_ring_forward_fp16(cfg, opts):
             dcn.dcnv4_set_option(k, 1 if k == "xcd_remap" else 0)
 
 
-def test_ring_forward_is_the_default_for_fp16_groups_of_16():
-    check_forward(CONFIGS["c1"], "f16")
+def test_ring_forward_is_the_default_for_fp16_groups_of_16_on_maps_of_many_batches():
+    check_forward(Config("ringdef", N=2, H=24, W=30, C=32, G=2), "f16")
     assert dcn.dcnv4_last_kernel_name(0).startswith("dcnv4_ring_fwd_kernel<")
+    check_forward(CONFIGS["c1"], "f16")            # 14x14: four batches per image, rectangle kernel
+    assert dcn.dcnv4_last_kernel_name(0).startswith("dcnv4_tiled_kernel<")
 
 
 def _random_cases(n, seed):
