@@ -63,7 +63,7 @@ def test_backward_argument_validation_happens_on_the_host():
     ptrs[4] = A + 4
     assert bwd(lib, tuple(ptrs)) == 4
     assert bwd(lib, k=(3, 5)) == 3
-    assert bwd(lib, dtype=1, Cg=32) == 3                          # fp16 backward exists for Cg 8 and 16 only
+    assert bwd(lib, dtype=1, Cg=64) == 3                          # fp16 backward exists for Cg 8, 16 and 32 only
     assert bwd(lib, N=-1) == 2
 
 
