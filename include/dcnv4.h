@@ -20,14 +20,19 @@
  *   offset, grad_offset  [N, Ho, Wo, G, 9, 2]
  *   mask, grad_mask      [N, Ho, Wo, G, 9]
  *   y, grad_y            [N, Ho, Wo, G*Cg]
+ *   offset_mask, grad_offset_mask  [N, Ho, Wo, G, 32]   (the *_merged entry points: per (pixel, group)
+ *                        the 18 offsets, then the 9 mask values, then 5 unused entries)
  * with (Ho, Wo) as returned by dcnv4_output_hw().  The library allocates nothing and
- * keeps nothing between calls except the tuning options below; it enqueues its kernels
+ * keeps nothing between calls except the test switches below; it enqueues its kernels
  * on `stream` (a hipStream_t, NULL = the default stream) and returns without
  * synchronising.  Outputs must not alias inputs.
  *
  * Supported: kernel 3x3; stride, dilation >= 1; pad >= 0; Cg in {8, 16, 32, 64};
- * dtype F32 or F16 (fp16 storage, fp32 positions, weights and accumulation, one
- * round-to-nearest at the store); the fp16 backward exists for Cg 8 and 16.  Byte
+ * dtype F32 or F16.  F16 is fp16 storage with fp32 positions and accumulation and one
+ * round-to-nearest at the store; where the forward runs out of its ring of input rows
+ * in LDS (fp16, Cg 16, maps of several hundred pixels) the four products m * corner
+ * weight of a tap are rounded to fp16 before they multiply the (fp16) inputs; products
+ * and sums stay fp32.  The fp16 backward exists for Cg 8, 16 and 32.  Byte
  * offsets inside one image are 32-bit: one image of x and of y, and the farthest
  * clamped sampling position (about twice the image extent), must stay below 2 GiB;
  * larger images are refused with DCNV4_ERR_UNSUPPORTED.
@@ -68,22 +73,47 @@ int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y,
                   int pad_h, int pad_w, int dil_h, int dil_w,
                   float offset_scale, int dtype, void *stream);
 
+/* The same with offsets and mask values in ONE buffer [N,Ho,Wo,G,32], as the single linear layer of
+ * Sec. 3.2 "Micro design" (offset and mask projections merged, output padded to a multiple of 8 per
+ * group for aligned access) emits it: entries 0..17 of a (pixel, group) are its offsets (tap-major,
+ * width then height), 18..26 its mask values, 27..31 are ignored.  Runs through the LDS-staged
+ * kernels only; a shape none of them takes is refused with DCNV4_ERR_UNSUPPORTED. */
+int dcnv4_forward_merged(const void *x, const void *offset_mask, void *y,
+                         int N, int H, int W, int G, int Cg,
+                         int kernel_h, int kernel_w, int stride_h, int stride_w,
+                         int pad_h, int pad_w, int dil_h, int dil_w,
+                         float offset_scale, int dtype, void *stream);
+
 /* Backward of Eq. 1 by the chain rule (the paper gives no backward):
  *   grad_mask_k  = sum_c gy[c] * S_k[c]
  *   grad_offset  = offset_scale * m_k * sum_c gy[c] * dS_k[c]/d(wx, hy)   (right-hand derivative
  *                  at whole-number coordinates)
  *   grad_x      += m_k * corner weight * gy[c]   at the in-image neighbours
- * Overwrites all three outputs; grad_x is zero-filled on `stream` first.  Sums are fp32; in F16
- * grad_offset/grad_mask are rounded once, grad_x receives its per-tile fp32 sums through packed
- * fp16 atomics (a pixel is touched by the few tiles that reach it).  With Cg 32 or 64 (fp32) the
- * group's channels are processed in slices and grad_offset/grad_mask are summed with fp32 atomics,
- * so their last bits can differ between runs, like grad_x's. */
+ * Overwrites all three outputs; grad_x is zero-filled on `stream` first.  grad_offset/grad_mask are
+ * fp32 sums, rounded once in F16.  In the LDS-staged path grad_x is summed per tile in 32-bit fixed
+ * point with 22 fractional bits (every term m * weight * gy[c] rounded to a multiple of 2^-22, the
+ * sum itself exact and independent of the order); terms of magnitude 64 or more, and whatever would
+ * take a tile's sum for one pixel beyond 512, are added straight to memory in fp32 instead.  The
+ * tile sums (a pixel is touched by the few tiles that reach it) go to memory through fp32 atomics,
+ * packed fp16 atomics in F16.  With Cg 32 or 64 (fp32) the group's channels are processed in slices
+ * and grad_offset/grad_mask are summed with fp32 atomics, so their last bits can differ between
+ * runs, like grad_x's. */
 int dcnv4_backward(const void *x, const void *offset, const void *mask, const void *grad_y,
                    void *grad_x, void *grad_offset, void *grad_mask,
                    int N, int H, int W, int G, int Cg,
                    int kernel_h, int kernel_w, int stride_h, int stride_w,
                    int pad_h, int pad_w, int dil_h, int dil_w,
                    float offset_scale, int dtype, void *stream);
+
+/* dcnv4_backward for the merged buffer of Sec. 3.2 "Micro design": grad_offset_mask has the layout of
+ * offset_mask (gradients of the 18 offsets, of the 9 mask values, 5 zeros); it is zero-filled on
+ * `stream` first, like grad_x.  Same restrictions as dcnv4_forward_merged. */
+int dcnv4_backward_merged(const void *x, const void *offset_mask, const void *grad_y,
+                          void *grad_x, void *grad_offset_mask,
+                          int N, int H, int W, int G, int Cg,
+                          int kernel_h, int kernel_w, int stride_h, int stride_w,
+                          int pad_h, int pad_w, int dil_h, int dil_w,
+                          float offset_scale, int dtype, void *stream);
 
 /* Bytes the ideal memory-access model of Sec. 3.2 ("2HWC + 27HWG", every value touched
  * once) assigns to one forward call: x + offset + mask + y.  Host-only helper. */
@@ -95,28 +125,35 @@ long long dcnv4_forward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
 long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg,
                                            int H_out, int W_out, int dtype);
 
-/* Tuning knobs for benchmarking (process-wide, not thread-safe); value 0 restores the default.
- *   "fwd_path"    1 = direct global gather, 2 = input window staged in LDS, 0 = staged where a
+/* The two models with the merged buffer: 32 instead of 27 values per (pixel, group). */
+long long dcnv4_forward_merged_algorithmic_bytes(int N, int H, int W, int G, int Cg,
+                                                 int H_out, int W_out, int dtype);
+long long dcnv4_backward_merged_algorithmic_bytes(int N, int H, int W, int G, int Cg,
+                                                  int H_out, int W_out, int dtype);
+
+/* TEST AND BENCHMARK SWITCHES, not an application interface: they force a kernel or a tile shape so
+ * that every path can be checked on every shape (process-wide, not thread-safe).  An application
+ * never calls this; the library's own choice is the value 0 of every switch.
+ *   "reset"       (any value) puts every switch back to 0
+ *   "fwd_path"    1 = direct global gather, 2 = input rectangle staged in LDS, 3 = ring of input rows
+ *                 in LDS (fp16, Cg 16); 0 = ring on maps of 512 pixels or more, else rectangle where a
  *                 useful tile fits, else direct
- *   "bwd_path"    1 = one kernel with global atomics for grad_x, 2 = two LDS-staged kernels (gathers
- *                 for grad_offset/grad_mask; LDS-private accumulation of grad_x), 0 = staged where
- *                 it applies (Cg up to 16, wider fp32 groups as 64-byte channel slices, and a useful
- *                 tile fits), else the first
+ *   "bwd_path"    1 = one kernel with global atomics for grad_x (fp32), 2 = two LDS-staged kernels
+ *                 (gathers for grad_offset/grad_mask; fixed-point accumulation of grad_x in LDS),
+ *                 0 = staged where a useful tile fits, else the first
  *   "fwd_single"  LDS rectangle buffers of the staged gather kernels: 1 = always two (the next tile
  *                 streams in during the current one), 2 = always one (bigger rectangle, refilled
  *                 between tiles), 0 = whichever the tile chooser estimates to be cheaper
- *   "wg_per_cu"   persistent workgroups per compute unit of the staged kernels (1..16, as far as LDS
- *                 allows); default 8 / 2 for the one- / four-wave forward, else 1
+ *   "wg_per_cu"   persistent workgroups per compute unit of the rectangle kernels (1..16, as far as
+ *                 LDS allows)
  *   "gom_coop"    1 = the fp32 grad_offset/grad_mask pass moves its values through per-wave LDS slices
  *                 even for whole groups (default: each lane reads and writes its own pixel's values)
- *   "batch_order" how a tile's batches go to the waves in the staged kernels: 1 interleaved, 2 in
- *                 contiguous runs (default: runs in the grad_x pass, interleaved elsewhere)
  *   "gx_threads"  workgroup size of the staged grad_x kernel (256, 512 or 768)
- *   "halo"        displacement in pixels that the staged window allows for (default 6, 4 in the grad_x
- *                 pass; tiles that hold a whole image have no use for it);
- *                 samples beyond it are still exact, they take the global path
- *   "lds_kb"      LDS budget per workgroup of the staged kernel (8..160)
- *   "fwd_threads" workgroup size of the staged forward (64, 256, 512 or 768; default by tile size)
+ *   "halo"        displacement in pixels (rows, for the ring) that the staged window allows for;
+ *                 samples beyond it are still exact, they take the path through global memory
+ *   "lds_kb"      LDS budget per workgroup of the staged kernels (8..160)
+ *   "fwd_threads" workgroup size of the staged forward (64, 128, 256, 512, 640 or 768 for the
+ *                 rectangle kernel; 256 = four waves instead of eight for the ring)
  *   "fwd_cpt"     channels per thread in the direct forward kernel (8 or 16)
  *   "bwd_cpt"     channels per thread in the direct backward kernel (1, 2, 4, 8 or 16)
  *   "xcd_remap"   1 = hand consecutive tiles to one XCD (default), 0 = plain block order

@@ -15,8 +15,9 @@ DCNV4_OK = 0
 
 # every symbol include/dcnv4.h declares
 EXPORTS = (
-    "dcnv4_output_hw", "dcnv4_forward", "dcnv4_backward",
+    "dcnv4_output_hw", "dcnv4_forward", "dcnv4_backward", "dcnv4_forward_merged", "dcnv4_backward_merged",
     "dcnv4_forward_algorithmic_bytes", "dcnv4_backward_algorithmic_bytes",
+    "dcnv4_forward_merged_algorithmic_bytes", "dcnv4_backward_merged_algorithmic_bytes",
     "dcnv4_set_option", "dcnv4_last_kernel_name", "dcnv4_status_string",
 )
 
@@ -48,7 +49,12 @@ def load_library():
     lib.dcnv4_forward.restype = ci
     lib.dcnv4_backward.argtypes = [vp] * 7 + geo
     lib.dcnv4_backward.restype = ci
-    for f in (lib.dcnv4_forward_algorithmic_bytes, lib.dcnv4_backward_algorithmic_bytes):
+    lib.dcnv4_forward_merged.argtypes = [vp] * 3 + geo
+    lib.dcnv4_forward_merged.restype = ci
+    lib.dcnv4_backward_merged.argtypes = [vp] * 5 + geo
+    lib.dcnv4_backward_merged.restype = ci
+    for f in (lib.dcnv4_forward_algorithmic_bytes, lib.dcnv4_backward_algorithmic_bytes,
+              lib.dcnv4_forward_merged_algorithmic_bytes, lib.dcnv4_backward_merged_algorithmic_bytes):
         f.argtypes = [ci] * 8
         f.restype = ctypes.c_longlong
     lib.dcnv4_set_option.argtypes = [ctypes.c_char_p, ci]
@@ -95,6 +101,14 @@ def dcnv4_forward_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype):
 
 def dcnv4_backward_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype):
     return int(load_library().dcnv4_backward_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype))
+
+
+def dcnv4_forward_merged_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype):
+    return int(load_library().dcnv4_forward_merged_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype))
+
+
+def dcnv4_backward_merged_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype):
+    return int(load_library().dcnv4_backward_merged_algorithmic_bytes(N, H, W, G, Cg, Ho, Wo, dtype))
 
 
 def _dtype_code(t):
@@ -191,3 +205,69 @@ def dcnv4_backward(x, offset, mask, grad_y, kernel=3, stride=1, pad=1, dilation=
     if rc:
         raise Dcnv4Error(rc, "dcnv4_backward")
     return gx, go, gm
+
+
+def _merged_shape_args(x, om, kernel, stride, pad, dilation):
+    (kh, kw), (sh, sw), (ph, pw), (dh, dw) = map(_pair, (kernel, stride, pad, dilation))
+    if x.dim() != 4 or om.dim() != 5 or om.shape[4] != 32:
+        raise ValueError("dcnv4: expected x [N,H,W,C] and offset_mask [N,Ho,Wo,G,32]")
+    N, H, W, C = x.shape
+    G = om.shape[3]
+    if G < 1 or C % G:
+        raise ValueError("dcnv4: C must be a multiple of G")
+    Ho, Wo = dcnv4_output_hw(H, W, (kh, kw), (sh, sw), (ph, pw), (dh, dw))
+    if tuple(om.shape) != (N, Ho, Wo, G, 32):
+        raise ValueError(f"dcnv4: offset_mask shape {tuple(om.shape)} does not match N={N} Ho={Ho} Wo={Wo} G={G}")
+    return (N, H, W, G, C // G, kh, kw, sh, sw, ph, pw, dh, dw), (N, Ho, Wo, C)
+
+
+def dcnv4_forward_merged(x, offset_mask, kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0, out=None, stream=None,
+                         prepare_only=False):
+    """dcnv4_forward with the offsets and mask values in one tensor [N,Ho,Wo,G,32]: 18 offsets, 9 mask
+    values, 5 unused entries per (pixel, group)."""
+    import torch
+    geo, yshape = _merged_shape_args(x, offset_mask, kernel, stride, pad, dilation)
+    for name, t in (("x", x), ("offset_mask", offset_mask)):
+        _check(name, t, x)
+    if out is None:
+        out = torch.empty(yshape, dtype=x.dtype, device=x.device)
+    else:
+        _check("out", out, x)
+        if tuple(out.shape) != yshape:
+            raise ValueError("dcnv4: out has the wrong shape")
+    args = (x.data_ptr(), offset_mask.data_ptr(), out.data_ptr(), *geo,
+            float(offset_scale), _dtype_code(x), _stream_ptr(stream, x.device))
+    if prepare_only:
+        return args
+    with torch.cuda.device(x.device):
+        rc = load_library().dcnv4_forward_merged(*args)
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_forward_merged")
+    return out
+
+
+def dcnv4_backward_merged(x, offset_mask, grad_y, kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0,
+                          out=None, stream=None, prepare_only=False):
+    """(grad_x, grad_offset_mask) of dcnv4_forward_merged; grad_offset_mask is laid out like offset_mask."""
+    import torch
+    geo, yshape = _merged_shape_args(x, offset_mask, kernel, stride, pad, dilation)
+    for name, t in (("x", x), ("offset_mask", offset_mask), ("grad_y", grad_y)):
+        _check(name, t, x)
+    if tuple(grad_y.shape) != yshape:
+        raise ValueError("dcnv4: grad_y has the wrong shape")
+    if out is None:
+        out = (torch.empty_like(x), torch.empty_like(offset_mask))
+    gx, gom = out
+    for name, t, ref in (("grad_x", gx, x), ("grad_offset_mask", gom, offset_mask)):
+        _check(name, t, x)
+        if t.shape != ref.shape:
+            raise ValueError(f"dcnv4: {name} has the wrong shape")
+    args = (x.data_ptr(), offset_mask.data_ptr(), grad_y.data_ptr(), gx.data_ptr(), gom.data_ptr(), *geo,
+            float(offset_scale), _dtype_code(x), _stream_ptr(stream, x.device))
+    if prepare_only:
+        return args
+    with torch.cuda.device(x.device):
+        rc = load_library().dcnv4_backward_merged(*args)
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_backward_merged")
+    return gx, gom

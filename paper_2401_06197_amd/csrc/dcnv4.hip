@@ -536,6 +536,7 @@ struct Problem {
     int sh, sw, ph, pw, dh, dw;
     float scale;
     int dtype;
+    int merged;     // offsets and mask values share one buffer of 32 values per (pixel, group)
 };
 
 int validate(const Problem &q, int kh, int kw, const void *const *ptrs, int nptrs)
@@ -853,8 +854,14 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
     p.y_img_bytes = base.y_img_bytes;
     p.row_bytes = base.row_bytes;
     p.pix_bytes = base.pix_bytes;
-    p.off_img_bytes = (int)(pgi * 18 * es);
-    p.msk_img_bytes = (int)(pgi * 9 * es);
+    p.og_bytes = (int)((q.merged ? 32 : 18) * es);
+    p.mg_bytes = (int)((q.merged ? 32 : 9) * es);
+    if (pgi * p.og_bytes >= (1LL << 31))
+        return DCNV4_ERR_UNSUPPORTED;
+    p.off_img_bytes = (int)(pgi * p.og_bytes);
+    p.msk_img_bytes = (int)(pgi * p.mg_bytes);
+    p.off_ext_bytes = (int)((pgi - 1) * p.og_bytes + 18 * es);
+    p.msk_ext_bytes = (int)((pgi - 1) * p.mg_bytes + 9 * es);
     *out = p;
     return DCNV4_OK;
 }
@@ -937,7 +944,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
 template <typename T, int CG, int THREADS>
 int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
-    return launch_tiled<T, CG, THREADS, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0, g_opt.fwd_path == 2);
+    return launch_tiled<T, CG, THREADS, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0, g_opt.fwd_path == 2 || q.merged);
 }
 
 // The tiled kernel keeps Cg fp32 accumulators and 4*Cg input values per lane, so it is built
@@ -977,7 +984,7 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
                 if (make_tgeo(q, 256, kTiledFwd, &probe, CG, 1) == DCNV4_OK && probe.tiles_per_img == 1 &&
                     probe.R * probe.Q <= 16 * 64)
                     return launch_tiled<T, CG, 256, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0,
-                                                               g_opt.fwd_path == 2, 1, 3);
+                                                               g_opt.fwd_path == 2 || q.merged, 1, 3);
             }
             if (g_opt.fwd_threads == 512)
                 return launch_fwd_tiled<T, CG, 512>(x, off, msk, y, q, s);
@@ -1105,8 +1112,12 @@ int make_rgeo(const Problem &q, int waves, int grid_wgs, RGeo *out)
     p.y_img_bytes = base.y_img_bytes;
     p.row_bytes = base.row_bytes;
     p.pix_bytes = base.pix_bytes;
-    p.off_img_bytes = (int)(pgi * 36);
-    p.msk_img_bytes = (int)(pgi * 18);
+    p.og_bytes = q.merged ? 64 : 36;
+    p.mg_bytes = q.merged ? 64 : 18;
+    p.off_img_bytes = (int)(pgi * p.og_bytes);
+    p.msk_img_bytes = (int)(pgi * p.mg_bytes);
+    p.off_ext_bytes = (int)((pgi - 1) * p.og_bytes + 36);
+    p.msk_ext_bytes = (int)((pgi - 1) * p.mg_bytes + 18);
     *out = p;
     return DCNV4_OK;
 }
@@ -1168,6 +1179,8 @@ int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 2)
             return rc;
     }
+    if (q.merged)                            // (the direct kernels read the two tensors of the separate layout)
+        return DCNV4_ERR_UNSUPPORTED;
     const int cpt = pick_fwd_cpt(q.Cg);
     switch (q.Cg) {
     case 8: return dispatch_fwd_cpt<T, 8>(cpt, x, off, msk, y, q, s);
@@ -1236,7 +1249,7 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     if constexpr (sizeof(T) == 4)
         gom_direct = !sliced && g_opt.gom_coop == 0;
     // (for fp16 there is no other backward, so the tile-size heuristic does not apply)
-    const bool any_size = g_opt.bwd_path == 2 || sizeof(T) == 2;
+    const bool any_size = g_opt.bwd_path == 2 || sizeof(T) == 2 || q.merged;
     // the grad_x pass: twelve waves keep the LDS busiest (measured)
     const int gxt = g_opt.gx_threads ? g_opt.gx_threads : 768;
     TiledLaunch l_gom, l_gx;
@@ -1261,7 +1274,9 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
         hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)ptr, bytes);
     };
     zero(gx, (long long)q.N * l_gx.p.x_img_bytes);
-    if (sliced) {
+    if (q.merged) {
+        zero(go, (long long)q.N * l_gom.p.off_img_bytes);       // one buffer: gradients and padding
+    } else if (sliced) {
         zero(go, (long long)q.N * l_gom.p.off_img_bytes);
         zero(gm, (long long)q.N * l_gom.p.msk_img_bytes);
     }
@@ -1284,6 +1299,7 @@ int fill_problem(Problem *q, int N, int H, int W, int G, int Cg, int kh, int kw,
     q->N = N; q->H = H; q->W = W; q->G = G; q->Cg = Cg;
     q->sh = sh; q->sw = sw; q->ph = ph; q->pw = pw; q->dh = dh; q->dw = dw;
     q->scale = scale; q->dtype = dtype;
+    q->merged = 0;
     q->Ho = q->Wo = 0;
     if (H < 1 || W < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1)
         return DCNV4_ERR_SHAPE;
@@ -1311,47 +1327,59 @@ int dcnv4_output_hw(int H, int W, int kernel_h, int kernel_w, int stride_h, int 
     return DCNV4_OK;
 }
 
-int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y, int N, int H, int W, int G, int Cg,
-                  int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
-                  float offset_scale, int dtype, void *stream)
+namespace {
+
+int forward_impl(const void *x, const void *offset, const void *mask, void *y, int N, int H, int W, int G, int Cg,
+                 int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                 float offset_scale, int dtype, void *stream, bool merged)
 {
-    const void *ptrs[4] = {x, offset, mask, y};
-    for (const void *ptr : ptrs)
-        if (!ptr)
+    const void *ptrs[4] = {x, offset, y, mask};
+    for (int i = 0; i < (merged ? 3 : 4); ++i)
+        if (!ptrs[i])
             return DCNV4_ERR_NULL;
     Problem q;
     int rc = fill_problem(&q, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
                           offset_scale, dtype);
     if (rc)
         return rc;
-    rc = validate(q, kernel_h, kernel_w, ptrs, 4);
+    rc = validate(q, kernel_h, kernel_w, ptrs, merged ? 3 : 4);
     if (rc)
         return rc;
+    if (merged) {
+        // the mask values follow the 18 offsets of their (pixel, group) in the same buffer
+        q.merged = 1;
+        mask = (const char *)offset + 18 * esize(dtype);
+    }
     hipStream_t s = (hipStream_t)stream;
     return dtype == DCNV4_F16 ? dispatch_fwd<_Float16>(x, offset, mask, y, q, s)
                               : dispatch_fwd<float>(x, offset, mask, y, q, s);
 }
 
-int dcnv4_backward(const void *x, const void *offset, const void *mask, const void *grad_y, void *grad_x,
-                   void *grad_offset, void *grad_mask, int N, int H, int W, int G, int Cg, int kernel_h,
-                   int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
-                   float offset_scale, int dtype, void *stream)
+int backward_impl(const void *x, const void *offset, const void *mask, const void *grad_y, void *grad_x,
+                  void *grad_offset, void *grad_mask, int N, int H, int W, int G, int Cg, int kernel_h,
+                  int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                  float offset_scale, int dtype, void *stream, bool merged)
 {
-    const void *ptrs[7] = {x, offset, mask, grad_y, grad_x, grad_offset, grad_mask};
-    for (const void *ptr : ptrs)
-        if (!ptr)
+    const void *ptrs[7] = {x, offset, grad_y, grad_x, grad_offset, mask, grad_mask};
+    for (int i = 0; i < (merged ? 5 : 7); ++i)
+        if (!ptrs[i])
             return DCNV4_ERR_NULL;
     Problem q;
     int rc = fill_problem(&q, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
                           offset_scale, dtype);
     if (rc)
         return rc;
-    rc = validate(q, kernel_h, kernel_w, ptrs, 7);
+    rc = validate(q, kernel_h, kernel_w, ptrs, merged ? 5 : 7);
     if (rc)
         return rc;
+    if (merged) {
+        q.merged = 1;
+        mask = (const char *)offset + 18 * esize(dtype);
+        grad_mask = (char *)grad_offset + 18 * esize(dtype);
+    }
     hipStream_t s = (hipStream_t)stream;
     if (dtype == DCNV4_F16) {
-        // fp16 storage, fp32 arithmetic; only the LDS-staged kernels exist for it (Cg 8 or 16)
+        // fp16 storage, fp32 arithmetic; only the LDS-staged kernels exist for it (Cg 8, 16 or 32)
         if (g_opt.bwd_path == 1)
             return DCNV4_ERR_UNSUPPORTED;
         if (Cg == 8)
@@ -1362,13 +1390,13 @@ int dcnv4_backward(const void *x, const void *offset, const void *mask, const vo
             return launch_bwd_tiled<_Float16, 32>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         return DCNV4_ERR_UNSUPPORTED;
     }
-    if (g_opt.bwd_path != 1) {
+    if (g_opt.bwd_path != 1 || merged) {
         rc = DCNV4_ERR_UNSUPPORTED;
         if (Cg == 8)
             rc = launch_bwd_tiled<float, 8>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         else if (Cg == 16 || Cg == 32 || Cg == 64)     // wider groups: 64-byte channel slices
             rc = launch_bwd_tiled<float, 16>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
-        if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.bwd_path == 2)
+        if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.bwd_path == 2 || merged)
             return rc;
     }
     const int cpt = pick_bwd_cpt(Cg);
@@ -1379,6 +1407,42 @@ int dcnv4_backward(const void *x, const void *offset, const void *mask, const vo
     case 64: return dispatch_bwd_cpt<64>(cpt, x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
     }
     return DCNV4_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y, int N, int H, int W, int G, int Cg,
+                  int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                  float offset_scale, int dtype, void *stream)
+{
+    return forward_impl(x, offset, mask, y, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h,
+                        dil_w, offset_scale, dtype, stream, false);
+}
+
+int dcnv4_forward_merged(const void *x, const void *offset_mask, void *y, int N, int H, int W, int G, int Cg,
+                         int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h,
+                         int dil_w, float offset_scale, int dtype, void *stream)
+{
+    return forward_impl(x, offset_mask, nullptr, y, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w,
+                        dil_h, dil_w, offset_scale, dtype, stream, true);
+}
+
+int dcnv4_backward(const void *x, const void *offset, const void *mask, const void *grad_y, void *grad_x,
+                   void *grad_offset, void *grad_mask, int N, int H, int W, int G, int Cg, int kernel_h,
+                   int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                   float offset_scale, int dtype, void *stream)
+{
+    return backward_impl(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, N, H, W, G, Cg, kernel_h, kernel_w,
+                         stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype, stream, false);
+}
+
+int dcnv4_backward_merged(const void *x, const void *offset_mask, const void *grad_y, void *grad_x,
+                          void *grad_offset_mask, int N, int H, int W, int G, int Cg, int kernel_h, int kernel_w,
+                          int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float offset_scale,
+                          int dtype, void *stream)
+{
+    return backward_impl(x, offset_mask, nullptr, grad_y, grad_x, grad_offset_mask, nullptr, N, H, W, G, Cg, kernel_h,
+                         kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype, stream, true);
 }
 
 long long dcnv4_forward_algorithmic_bytes(int N, int H, int W, int G, int Cg, int H_out, int W_out, int dtype)
@@ -1393,6 +1457,20 @@ long long dcnv4_backward_algorithmic_bytes(int N, int H, int W, int G, int Cg, i
     const long long es = esize(dtype), C = (long long)G * Cg;
     const long long P = (long long)N * H_out * W_out;
     return es * (2 * (long long)N * H * W * C + P * C + 2 * P * G * 27);
+}
+
+long long dcnv4_forward_merged_algorithmic_bytes(int N, int H, int W, int G, int Cg, int H_out, int W_out, int dtype)
+{
+    const long long es = esize(dtype), C = (long long)G * Cg;
+    const long long P = (long long)N * H_out * W_out;
+    return es * ((long long)N * H * W * C + P * C + P * G * 32);
+}
+
+long long dcnv4_backward_merged_algorithmic_bytes(int N, int H, int W, int G, int Cg, int H_out, int W_out, int dtype)
+{
+    const long long es = esize(dtype), C = (long long)G * Cg;
+    const long long P = (long long)N * H_out * W_out;
+    return es * (2 * (long long)N * H * W * C + P * C + 2 * P * G * 32);
 }
 
 int dcnv4_set_option(const char *key, int value)

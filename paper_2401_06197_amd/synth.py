@@ -87,3 +87,14 @@ def make_inputs(cfg: Config, dtype: str = "f32", seed: int = 0, integer_fraction
     out = {"x": x, "offset": off, "mask": m, "grad_y": gy}
     np_dtype = {"f32": np.float32, "f16": np.float16}[dtype]
     return {k: v.numpy().astype(np_dtype) for k, v in out.items()}
+
+
+def merge_offset_mask(offset, mask, pad_value=0.0):
+    """Pack offset [N,Ho,Wo,G,9,2] and mask [N,Ho,Wo,G,9] into one [N,Ho,Wo,G,32] array: 18 offsets,
+    9 mask values, 5 entries of pad_value (what one linear layer with 32 outputs per group would
+    hand over; the operator must ignore the last five)."""
+    N, Ho, Wo, G, K = mask.shape
+    om = np.full((N, Ho, Wo, G, 32), pad_value, dtype=mask.dtype)
+    om[..., :2 * K] = offset.reshape(N, Ho, Wo, G, 2 * K)
+    om[..., 2 * K:3 * K] = mask
+    return om

@@ -8,7 +8,7 @@ import torch
 
 import oracle
 from paper_2401_06197_amd import binding as dcn
-from paper_2401_06197_amd.synth import CONFIGS, Config, make_inputs
+from paper_2401_06197_amd.synth import CONFIGS, Config, make_inputs, merge_offset_mask
 
 pytestmark = pytest.mark.gpu
 
@@ -89,6 +89,51 @@ def test_c5_shape_backward_fp16():
     """fp16 storage with fp32 arithmetic; grad_x collects its fp32 tile sums with packed fp16 atomics."""
     check_backward(CONFIGS["c5"], dtype="f16")
     check_backward(CONFIGS["c1"], dtype="f16")
+
+
+# ------------------------------------------------------------------ offsets and mask values in one buffer
+def check_merged(cfg, dtype, seed=0, backward=True):
+    """Same inputs through dcnv4_forward_merged / dcnv4_backward_merged ([N,Ho,Wo,G,32] buffer whose five
+    unused entries per group hold a large number that must not leak into any result) against the oracle's
+    unpacking wrapper."""
+    t = make_inputs(cfg, dtype, seed=seed)
+    om = merge_offset_mask(t["offset"], t["mask"], pad_value=777.0)
+    d = to_gpu({"x": t["x"], "om": om, "grad_y": t["grad_y"]}, dtype)
+    y = dcn.dcnv4_forward_merged(d["x"], d["om"], **geo_kw(cfg))
+    torch.cuda.synchronize()
+    close(f"{cfg.name}/{dtype}/merged/y", y.cpu().numpy(), oracle.forward_merged(t["x"], om, **geo_kw(cfg)), TOL[dtype])
+    if not backward:
+        return
+    out = (torch.full_like(d["x"], 7.0), torch.full_like(d["om"], 7.0))
+    gx, gom = dcn.dcnv4_backward_merged(d["x"], d["om"], d["grad_y"], out=out, **geo_kw(cfg))
+    torch.cuda.synchronize()
+    rgx, rgom = oracle.backward_merged(t["x"], om, t["grad_y"], **geo_kw(cfg))
+    close(f"{cfg.name}/{dtype}/merged/grad_offset_mask", gom.cpu().numpy(), rgom, TOL[dtype])
+    close(f"{cfg.name}/{dtype}/merged/grad_x", gx.cpu().numpy(), rgx, TOL[dtype])
+    assert torch.all(gom[..., 27:] == 0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_merged_buffer_c1_c2_c5(dtype):
+    check_merged(CONFIGS["c1"], dtype)
+    check_merged(CONFIGS["c5"], dtype)          # (c2 is the same shape: forward and backward, full size)
+
+
+MERGED = [Config("m_rag", N=3, H=13, W=11, C=48, G=3), Config("m_cg8", N=2, H=10, W=12, C=24, G=3),
+          Config("m_cg32", N=2, H=12, W=9, C=96, G=3), Config("m_s2", N=2, H=15, W=14, C=32, G=2, stride=2),
+          Config("m_ring", N=2, H=24, W=30, C=32, G=2), Config("m_one", N=2, H=1, W=1, C=16, G=1),
+          Config("m_cg64", N=1, H=8, W=8, C=128, G=2)]
+
+
+@pytest.mark.parametrize("cfg", MERGED, ids=[c.name for c in MERGED])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_merged_buffer_geometries(cfg, dtype):
+    check_merged(cfg, dtype, seed=41, backward=not (dtype == "f16" and cfg.Cg == 64))
+
+
+@pytest.mark.parametrize("name", ["c3_28", "c3_14", "c3_7", "c4", "paper_56x56x128"])
+def test_merged_buffer_forward_fp16_other_workloads(name):
+    check_merged(CONFIGS[name], "f16", backward=False)
 
 
 # ------------------------------------------------------------------ the paper's own benchmark shapes
