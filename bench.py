@@ -28,7 +28,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets rotated per leg")
-    ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16")
+    ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16,fwd_f16_merged,bwd_f32_merged",
+                    help="fwd|bwd _ f16|f32 [_merged: offsets and mask values in one [N,Ho,Wo,G,32] buffer]")
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--more-workloads", default="c3_28,c3_14,c3_7,c4",
                     help="further workloads whose fp16 forward is timed and reported under legs as fwd_f16@<name>")
@@ -118,27 +119,43 @@ def time_leg(torch, stream, launch, nsets, steps, warmup, cold_only=False):
 
 def run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_output=False):
     """Times one leg ("fwd_f16", "bwd_f32", ...) on workload cfg; returns (record, first output or None)."""
-    from paper_2401_06197_amd.synth import make_inputs
+    from paper_2401_06197_amd.synth import make_inputs, merge_offset_mask
     dev = torch.device("cuda:0")
     Ho, Wo = cfg.out_hw
     out_elems = cfg.N * Ho * Wo * cfg.C
     geo = dict(kernel=cfg.kernel, stride=cfg.stride, pad=cfg.pad, dilation=cfg.dilation, offset_scale=cfg.offset_scale)
-    direction, dt = leg.split("_")
+    direction, dt = leg.split("_")[:2]
+    merged = leg.endswith("_merged")
     tdt = {"f16": torch.float16, "f32": torch.float32}[dt]
     code = {"f16": dcn.DCNV4_F16, "f32": dcn.DCNV4_F32}[dt]
     if (cfg.name, dt) not in host_inputs:
         host_inputs[(cfg.name, dt)] = make_inputs(cfg, dt, seed=0)
     base = {k: torch.from_numpy(v).to(dev) for k, v in host_inputs[(cfg.name, dt)].items()}
+    if merged:
+        h = host_inputs[(cfg.name, dt)]
+        base = {"x": base["x"], "grad_y": base["grad_y"], "om": torch.from_numpy(merge_offset_mask(h["offset"], h["mask"])).to(dev)}
     # enough buffer sets that a launch does not find its inputs in the 256 MB memory-side cache
     one_set = sum(v.numel() * v.element_size() for v in base.values())
     nsets = max(a.sets, min(16, -(-(320 << 20) // one_set)))
     sets = [base] + [{k: v.clone() for k, v in base.items()} for _ in range(nsets - 1)]
     if direction == "fwd":
         outs = [torch.empty((cfg.N, Ho, Wo, cfg.C), dtype=tdt, device=dev) for _ in range(nsets)]
-        alg = dcn.dcnv4_forward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
-        argv = [dcn.dcnv4_forward(s["x"], s["offset"], s["mask"], out=o, stream=stream, prepare_only=True, **geo)
+        if merged:
+            alg = dcn.dcnv4_forward_merged_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
+            argv = [dcn.dcnv4_forward_merged(s["x"], s["om"], out=o, stream=stream, prepare_only=True, **geo)
+                    for s, o in zip(sets, outs)]
+            fn = lib.dcnv4_forward_merged
+        else:
+            alg = dcn.dcnv4_forward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
+            argv = [dcn.dcnv4_forward(s["x"], s["offset"], s["mask"], out=o, stream=stream, prepare_only=True, **geo)
+                    for s, o in zip(sets, outs)]
+            fn = lib.dcnv4_forward
+    elif merged:
+        outs = [(torch.empty_like(s["x"]), torch.empty_like(s["om"])) for s in sets]
+        alg = dcn.dcnv4_backward_merged_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
+        argv = [dcn.dcnv4_backward_merged(s["x"], s["om"], s["grad_y"], out=o, stream=stream, prepare_only=True, **geo)
                 for s, o in zip(sets, outs)]
-        fn = lib.dcnv4_forward
+        fn = lib.dcnv4_backward_merged
     else:
         outs = [(torch.empty_like(s["x"]), torch.empty_like(s["offset"]), torch.empty_like(s["mask"])) for s in sets]
         alg = dcn.dcnv4_backward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
