@@ -73,11 +73,13 @@ int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y,
                   int pad_h, int pad_w, int dil_h, int dil_w,
                   float offset_scale, int dtype, void *stream);
 
-/* The same with offsets and mask values in ONE buffer [N,Ho,Wo,G,32], as the single linear layer of
- * Sec. 3.2 "Micro design" (offset and mask projections merged, output padded to a multiple of 8 per
- * group for aligned access) emits it: entries 0..17 of a (pixel, group) are its offsets (tap-major,
- * width then height), 18..26 its mask values, 27..31 are ignored.  Runs through the LDS-staged
- * kernels only; a shape none of them takes is refused with DCNV4_ERR_UNSUPPORTED. */
+/* The same with offsets and mask values in ONE buffer [N,Ho,Wo,G,32].  Sec. 3.2 "Micro design" merges
+ * the two linear layers that produce offsets and mask values into one; this is the tensor such a
+ * layer hands over when its 27 outputs per group are padded to 32 (this library's choice: records
+ * of 64 bytes in fp16, 128 in fp32, never straddling more than two cache lines).  Entries 0..17 of
+ * a (pixel, group) are its offsets (tap-major, width then height), 18..26 its mask values, 27..31
+ * are ignored.  Runs through the LDS-staged kernels only; a shape none of them takes is refused
+ * with DCNV4_ERR_UNSUPPORTED. */
 int dcnv4_forward_merged(const void *x, const void *offset_mask, void *y,
                          int N, int H, int W, int G, int Cg,
                          int kernel_h, int kernel_w, int stride_h, int stride_w,
@@ -105,7 +107,7 @@ int dcnv4_backward(const void *x, const void *offset, const void *mask, const vo
                    int pad_h, int pad_w, int dil_h, int dil_w,
                    float offset_scale, int dtype, void *stream);
 
-/* dcnv4_backward for the merged buffer of Sec. 3.2 "Micro design": grad_offset_mask has the layout of
+/* dcnv4_backward for the merged buffer: grad_offset_mask has the layout of
  * offset_mask (gradients of the 18 offsets, of the 9 mask values, 5 zeros); it is zero-filled on
  * `stream` first, like grad_x.  Same restrictions as dcnv4_forward_merged. */
 int dcnv4_backward_merged(const void *x, const void *offset_mask, const void *grad_y,
