@@ -712,7 +712,7 @@ bool grant_lds(const void *kern, int lds, int (&granted)[kMaxDevices])
     return true;
 }
 
-bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool locks, bool with_slices,
+bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbuf, int pb, bool accum, bool with_slices,
                  int chan_slices, TGeo *out, double *cost_out = nullptr)
 {
     const int es = esize(q.dtype);
@@ -738,10 +738,10 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
         long long cols = (long long)(Q - 1) * q.sw + 2LL * q.dw + 2LL * halo + 2;
         if (cols > q.W + 4) cols = q.W + 4;
         // the rectangle buffers (each a multiple of 1 KiB) share what the slices leave, after
-        // a block of zeros (pitch + 2 pixels) or one lock dword per rectangle pixel
-        const long long zero_bytes = locks ? 16 : ((cols + kTiledZeroPixelsExtra) * pb + 15) & ~15LL;
+        // a block of zeros (pitch + 2 pixels) or one more dword per rectangle pixel (the bound words of the grad_x accumulator)
+        const long long zero_bytes = accum ? 16 : ((cols + kTiledZeroPixelsExtra) * pb + 15) & ~15LL;
         const long long budget_px =
-            ((((long long)lds_bytes - slices - zero_bytes) * pb / (pb + (locks ? 4 : 0)) / nbuf) & ~1023LL) / pb;
+            ((((long long)lds_bytes - slices - zero_bytes) * pb / (pb + (accum ? 4 : 0)) / nbuf) & ~1023LL) / pb;
         if (budget_px < 64)
             continue;
         const long long rows_max = budget_px / cols;
@@ -757,7 +757,7 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
             const long long bands = (q.Ho + R - 1) / R, Rlast = q.Ho - (bands - 1) * R;
             const long long b_full = (R * Q + 63) / 64, b_last = (Rlast * Q + 63) / 64;
             const double rounds_img = tiles_q * ((bands - 1) * (double)((b_full + waves - 1) / waves) +
-                                                 (double)((b_last + waves - 1) / waves) + (nbuf == 1 && !locks ? 6.0 : 4.0) * bands);
+                                                 (double)((b_last + waves - 1) / waves) + (nbuf == 1 && !accum ? 6.0 : 4.0) * bands);
             const long long tiles = (long long)q.N * q.G * chan_slices * bands * tiles_q;
             const double per_tile = rounds_img / (double)(bands * tiles_q);
             const double cost = (double)((tiles + cus - 1) / cus) * per_tile;
@@ -781,7 +781,7 @@ bool choose_tile(const Problem &q, int threads, int halo, int lds_bytes, int nbu
     return found;
 }
 
-// `mode`: kTiledGradX has a single LDS rectangle of Cg fp32 per pixel plus one lock dword per pixel;
+// `mode`: kTiledGradX has a single LDS rectangle of Cg + 1 dwords per pixel (fixed-point sums and a bound word);
 // kTiledGradOM additionally keeps per-wave slices for the offset/mask values.
 int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel = 0, int want_nbuf = 0)
 {
