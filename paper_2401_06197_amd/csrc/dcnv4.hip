@@ -1049,7 +1049,7 @@ int make_rgeo(const Problem &q, int waves, int grid_wgs, RGeo *out)
     p.tiles_per_xcd = (p.ntiles + kXcds - 1) / kXcds;
     p.remap = g_opt.xcd_remap;
     p.cbn = (p.pitch + 31) / 32;
-    p.max_groups_round = kRingMaxTasks * waves / p.cbn;
+    p.max_groups_round = kRingMaxTasks * ring_staging_waves(waves) / p.cbn;
     if (p.ring < 2 * kRingTaskRows || p.max_groups_round < 1)
         return DCNV4_ERR_UNSUPPORTED;
     // tiles the busiest workgroup walks
