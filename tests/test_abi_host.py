@@ -67,6 +67,31 @@ def test_backward_argument_validation_happens_on_the_host():
     assert bwd(lib, N=-1) == 2
 
 
+def fwd_m(lib, x=A, om=A, y=A, N=1, H=14, W=14, G=4, Cg=16, k=(3, 3), dtype=0):
+    return lib.dcnv4_forward_merged(x, om, y, N, H, W, G, Cg, k[0], k[1], 1, 1, 1, 1, 1, 1, 1.0, dtype, None)
+
+
+def bwd_m(lib, ptrs=(A,) * 5, N=1, H=14, W=14, G=4, Cg=16, k=(3, 3), dtype=0):
+    return lib.dcnv4_backward_merged(*ptrs, N, H, W, G, Cg, k[0], k[1], 1, 1, 1, 1, 1, 1, 1.0, dtype, None)
+
+
+def test_merged_entry_points_validate_on_the_host_too():
+    lib = dcn.load_library()
+    assert fwd_m(lib, x=None) == 1 and fwd_m(lib, om=None) == 1 and fwd_m(lib, y=None) == 1
+    assert fwd_m(lib, om=A + 8) == 4 and fwd_m(lib, N=0) == 2 and fwd_m(lib, k=(5, 5)) == 3 and fwd_m(lib, Cg=12) == 3
+    for i in range(5):
+        ptrs = [A] * 5
+        ptrs[i] = None
+        assert bwd_m(lib, tuple(ptrs)) == 1
+    ptrs = [A] * 5
+    ptrs[4] = A + 4
+    assert bwd_m(lib, tuple(ptrs)) == 4
+    assert bwd_m(lib, dtype=1, Cg=64) == 3 and bwd_m(lib, H=0) == 2
+    c2 = (64, 56, 56, 8, 16, 56, 56)
+    assert dcn.dcnv4_forward_merged_algorithmic_bytes(*c2, dcn.DCNV4_F16) == 2 * 64 * 56 * 56 * (2 * 128 + 32 * 8)
+    assert dcn.dcnv4_backward_merged_algorithmic_bytes(*c2, dcn.DCNV4_F32) == 4 * 64 * 56 * 56 * (3 * 128 + 64 * 8)
+
+
 def test_options():
     assert dcn.dcnv4_last_kernel_name(0) is None or dcn.dcnv4_last_kernel_name(0).startswith("dcnv4_fwd")
     for key, bad in (("fwd_cpt", 5), ("nonsense", 1), ("fwd_path", 4), ("bwd_path", 3), ("fwd_single", 3), ("wg_per_cu", 17), ("halo", 65), ("lds_kb", 4), ("fwd_threads", 100)):
