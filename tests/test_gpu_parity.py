@@ -385,6 +385,37 @@ def test_runs_on_a_side_stream():
     close("stream/y", y.cpu().numpy(), ref, TOL["f16"])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_non_finite_upstream_gradients_propagate_like_in_the_oracle(dtype):
+    """A NaN or an infinity in grad_y must reach exactly the gradient entries it reaches in the definition
+    (the fixed-point accumulation of grad_x sends such pixels through its fp32 path)."""
+    cfg = Config("nonfinite", N=1, H=20, W=24, C=32, G=2)
+    t = make_inputs(cfg, dtype, seed=77)
+    t["grad_y"][0, 5, 7, 3] = np.nan
+    t["grad_y"][0, 12, 20, 17] = np.inf
+    t["grad_y"][0, 18, 2, 30] = -np.inf
+    d = to_gpu(t, dtype)
+    gx, go, gm = dcn.dcnv4_backward(d["x"], d["offset"], d["mask"], d["grad_y"])
+    torch.cuda.synchronize()
+    rgx, rgo, rgm = oracle.backward(t["x"], t["offset"], t["mask"], t["grad_y"])
+    tol = TOL[dtype]
+    got = gx.cpu().numpy().astype(np.float64)
+    bad = ~np.isfinite(rgx)
+    assert bad.any()
+    assert np.array_equal(np.isnan(got), np.isnan(rgx)), "grad_x: NaN in other places than the oracle's"
+    assert np.array_equal(got[np.isinf(rgx)], rgx[np.isinf(rgx)]), "grad_x: infinities differ"
+    assert (np.abs(got[~bad] - rgx[~bad]) <= tol + tol * np.abs(rgx[~bad])).all(), "grad_x: finite entries off"
+    # grad_offset / grad_mask of every OTHER output pixel are untouched by the three poisoned ones (at those
+    # three, products of infinities and zeros make the comparison meaningless)
+    clean = np.ones(rgm.shape[:3], dtype=bool)
+    for h, w in ((5, 7), (12, 20), (18, 2)):
+        clean[0, h, w] = False
+    for name, g, ref in (("grad_offset", go, rgo), ("grad_mask", gm, rgm)):
+        g = g.cpu().numpy().astype(np.float64)[clean]
+        assert np.isfinite(g).all(), name
+        assert (np.abs(g - ref[clean]) <= tol + tol * np.abs(ref[clean])).all(), name
+
+
 def test_gpu_call_with_bad_arguments_returns_error_and_writes_nothing():
     cfg = Config("bad", N=1, H=8, W=8, C=32, G=2)
     d = to_gpu(make_inputs(cfg, "f32", seed=11), "f32")
