@@ -841,7 +841,7 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
     p.nblocks = (int)nblocks;
     p.blocks_per_xcd = (int)((nblocks + kXcds - 1) / kXcds);
     p.remap = g_opt.xcd_remap;
-    p.blocked = gradx;
+    p.blocked = 0;                          // (contiguous runs per wave leave waves without work when a tile has few batches)
     p.div_g = make_div((unsigned)q.G);
     p.div_s = make_div((unsigned)chan_slices);
     p.slices = chan_slices;
