@@ -58,7 +58,10 @@ def measured_traffic(leg, workload, kernel=None):
     """HBM bytes per launch of the leg's kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
     (scaled by a copy of known size); read from the committed profile summary.  None if there is no
     summary, or if it was taken on another kernel than the one that ran now (`kernel`)."""
+    # (c5, the training-step config, is the c2 shape: the backward summaries carry its name)
     path = os.path.join(ROOT, "profiles", f"{leg}_{workload}_hbm_traffic.md")
+    if not os.path.exists(path) and workload == "c2":
+        path = os.path.join(ROOT, "profiles", f"{leg}_c5_hbm_traffic.md")
     traffic, profiled = None, None
     try:
         for line in open(path):
