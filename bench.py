@@ -28,8 +28,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets rotated per leg")
-    ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16,fwd_f16_merged,bwd_f32_merged",
-                    help="fwd|bwd _ f16|f32 [_merged: offsets and mask values in one [N,Ho,Wo,G,32] buffer]")
+    ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16,fwd_f16_merged,bwd_f32_merged,fwd_f16_softmax,bwd_f32_softmax",
+                    help="fwd|bwd _ f16|f32 [_merged: offsets and mask values in one [N,Ho,Wo,G,32] buffer | "
+                         "_softmax: the mask tensor holds logits, normalised over the 9 taps (DCNv3 form)]")
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--more-workloads", default="c3_28,c3_14,c3_7,c4",
                     help="further workloads whose fp16 forward is timed and reported under legs as fwd_f16@<name>")
@@ -129,6 +130,7 @@ def run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_outpu
     geo = dict(kernel=cfg.kernel, stride=cfg.stride, pad=cfg.pad, dilation=cfg.dilation, offset_scale=cfg.offset_scale)
     direction, dt = leg.split("_")[:2]
     merged = leg.endswith("_merged")
+    softmax = leg.endswith("_softmax")
     tdt = {"f16": torch.float16, "f32": torch.float32}[dt]
     code = {"f16": dcn.DCNV4_F16, "f32": dcn.DCNV4_F32}[dt]
     if (cfg.name, dt) not in host_inputs:
@@ -152,7 +154,7 @@ def run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_outpu
             alg = dcn.dcnv4_forward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
             argv = [dcn.dcnv4_forward(s["x"], s["offset"], s["mask"], out=o, stream=stream, prepare_only=True, **geo)
                     for s, o in zip(sets, outs)]
-            fn = lib.dcnv4_forward
+            fn = lib.dcnv4_forward_softmax if softmax else lib.dcnv4_forward
     elif merged:
         outs = [(torch.empty_like(s["x"]), torch.empty_like(s["om"])) for s in sets]
         alg = dcn.dcnv4_backward_merged_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
@@ -164,7 +166,7 @@ def run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_outpu
         alg = dcn.dcnv4_backward_algorithmic_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, Ho, Wo, code)
         argv = [dcn.dcnv4_backward(s["x"], s["offset"], s["mask"], s["grad_y"], out=o, stream=stream,
                                    prepare_only=True, **geo) for s, o in zip(sets, outs)]
-        fn = lib.dcnv4_backward
+        fn = lib.dcnv4_backward_softmax if softmax else lib.dcnv4_backward
 
     def launch(i):
         rc = fn(*argv[i])

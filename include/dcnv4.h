@@ -117,6 +117,26 @@ int dcnv4_backward_merged(const void *x, const void *offset_mask, const void *gr
                           int pad_h, int pad_w, int dil_h, int dil_w,
                           float offset_scale, int dtype, void *stream);
 
+/* The DCNv3 form of Eq. 1 (Sec. 3.1: there the K modulation scalars of a sampling location are
+ * softmax-normalised; DCNv4 removes exactly this): `mask_logits` [N,Ho,Wo,G,9] holds logits, and
+ * m = softmax over the 9 taps is formed inside the kernels, in registers, before the aggregation
+ * (expf of the shifted logits in fp32).  Everything else as in dcnv4_forward.  Runs through the
+ * input-rectangle kernels only; a shape they do not take is refused with DCNV4_ERR_UNSUPPORTED. */
+int dcnv4_forward_softmax(const void *x, const void *offset, const void *mask_logits, void *y,
+                          int N, int H, int W, int G, int Cg,
+                          int kernel_h, int kernel_w, int stride_h, int stride_w,
+                          int pad_h, int pad_w, int dil_h, int dil_w,
+                          float offset_scale, int dtype, void *stream);
+
+/* Backward of dcnv4_forward_softmax: grad_x and grad_offset as in dcnv4_backward with the normalised
+ * m; grad_mask_logits[k] = m_k * (g_k - sum_j m_j * g_j), g being the gradient w.r.t. m. */
+int dcnv4_backward_softmax(const void *x, const void *offset, const void *mask_logits, const void *grad_y,
+                           void *grad_x, void *grad_offset, void *grad_mask_logits,
+                           int N, int H, int W, int G, int Cg,
+                           int kernel_h, int kernel_w, int stride_h, int stride_w,
+                           int pad_h, int pad_w, int dil_h, int dil_w,
+                           float offset_scale, int dtype, void *stream);
+
 /* Bytes the ideal memory-access model of Sec. 3.2 ("2HWC + 27HWG", every value touched
  * once) assigns to one forward call: x + offset + mask + y.  Host-only helper. */
 long long dcnv4_forward_algorithmic_bytes(int N, int H, int W, int G, int Cg,

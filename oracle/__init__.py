@@ -130,3 +130,25 @@ def backward_merged(x, om, grad_y, **kw):
     gom[..., :2 * K] = go.reshape(go.shape[:4] + (2 * K,))
     gom[..., 2 * K:3 * K] = gm
     return gx, gom
+
+
+def softmax_taps(logits):
+    """Softmax over the last axis (the K sampling points), in double precision."""
+    z = _f64(logits)
+    e = np.exp(z - z.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def forward_softmax(x, offset, mask_logits, **kw):
+    """The DCNv3 form of Eq. 1 (Sec. 3.1): the modulation scalars are softmax-normalised over the K points
+    before the aggregation.  Written out as that definition: normalise, then forward()."""
+    return forward(x, offset, softmax_taps(mask_logits), **kw)
+
+
+def backward_softmax(x, offset, mask_logits, grad_y, **kw):
+    """Gradients of forward_softmax(): grad_x and grad_offset as in backward() with the normalised m; the
+    gradient w.r.t. logit k is m_k * (g_k - sum_j m_j g_j), g being the gradient w.r.t. m."""
+    m = softmax_taps(mask_logits)
+    gx, go, gm = backward(x, offset, m, grad_y, **kw)
+    gl = m * (gm - (m * gm).sum(axis=-1, keepdims=True))
+    return gx, go, gl

@@ -16,6 +16,7 @@ DCNV4_OK = 0
 # every symbol include/dcnv4.h declares
 EXPORTS = (
     "dcnv4_output_hw", "dcnv4_forward", "dcnv4_backward", "dcnv4_forward_merged", "dcnv4_backward_merged",
+    "dcnv4_forward_softmax", "dcnv4_backward_softmax",
     "dcnv4_forward_algorithmic_bytes", "dcnv4_backward_algorithmic_bytes",
     "dcnv4_forward_merged_algorithmic_bytes", "dcnv4_backward_merged_algorithmic_bytes",
     "dcnv4_set_option", "dcnv4_last_kernel_name", "dcnv4_status_string",
@@ -49,6 +50,10 @@ def load_library():
     lib.dcnv4_forward.restype = ci
     lib.dcnv4_backward.argtypes = [vp] * 7 + geo
     lib.dcnv4_backward.restype = ci
+    lib.dcnv4_forward_softmax.argtypes = [vp] * 4 + geo
+    lib.dcnv4_forward_softmax.restype = ci
+    lib.dcnv4_backward_softmax.argtypes = [vp] * 7 + geo
+    lib.dcnv4_backward_softmax.restype = ci
     lib.dcnv4_forward_merged.argtypes = [vp] * 3 + geo
     lib.dcnv4_forward_merged.restype = ci
     lib.dcnv4_backward_merged.argtypes = [vp] * 5 + geo
@@ -153,7 +158,7 @@ def _shape_args(x, offset, mask, kernel, stride, pad, dilation):
 
 
 def dcnv4_forward(x, offset, mask, kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0, out=None, stream=None,
-                  prepare_only=False):
+                  prepare_only=False, _entry="dcnv4_forward"):
     """y [N,Ho,Wo,C] = DCNv4 aggregation of x [N,H,W,C] (Eq. 1-2 of the paper, no softmax).
 
     With prepare_only the checked argument tuple for load_library().dcnv4_forward is returned
@@ -173,14 +178,24 @@ def dcnv4_forward(x, offset, mask, kernel=3, stride=1, pad=1, dilation=1, offset
     if prepare_only:
         return args
     with torch.cuda.device(x.device):
-        rc = load_library().dcnv4_forward(*args)
+        rc = getattr(load_library(), _entry)(*args)
     if rc:
-        raise Dcnv4Error(rc, "dcnv4_forward")
+        raise Dcnv4Error(rc, _entry)
     return out
 
 
+def dcnv4_forward_softmax(x, offset, mask_logits, **kw):
+    """dcnv4_forward with m = softmax of mask_logits over the 9 taps (the DCNv3 form)."""
+    return dcnv4_forward(x, offset, mask_logits, _entry="dcnv4_forward_softmax", **kw)
+
+
+def dcnv4_backward_softmax(x, offset, mask_logits, grad_y, **kw):
+    """(grad_x, grad_offset, grad_mask_logits) of dcnv4_forward_softmax."""
+    return dcnv4_backward(x, offset, mask_logits, grad_y, _entry="dcnv4_backward_softmax", **kw)
+
+
 def dcnv4_backward(x, offset, mask, grad_y, kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0,
-                   out=None, stream=None, prepare_only=False):
+                   out=None, stream=None, prepare_only=False, _entry="dcnv4_backward"):
     """(grad_x, grad_offset, grad_mask) of dcnv4_forward for upstream gradient grad_y."""
     import torch
     geo, yshape = _shape_args(x, offset, mask, kernel, stride, pad, dilation)
@@ -201,9 +216,9 @@ def dcnv4_backward(x, offset, mask, grad_y, kernel=3, stride=1, pad=1, dilation=
     if prepare_only:
         return args
     with torch.cuda.device(x.device):
-        rc = load_library().dcnv4_backward(*args)
+        rc = getattr(load_library(), _entry)(*args)
     if rc:
-        raise Dcnv4Error(rc, "dcnv4_backward")
+        raise Dcnv4Error(rc, _entry)
     return gx, go, gm
 
 

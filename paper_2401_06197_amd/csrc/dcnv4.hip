@@ -537,6 +537,7 @@ struct Problem {
     float scale;
     int dtype;
     int merged;     // offsets and mask values share one buffer of 32 values per (pixel, group)
+    int softmax;    // the mask tensor holds logits, normalised over the 9 taps inside the kernels
 };
 
 int validate(const Problem &q, int kh, int kw, const void *const *ptrs, int nptrs)
@@ -854,6 +855,7 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
     p.y_img_bytes = base.y_img_bytes;
     p.row_bytes = base.row_bytes;
     p.pix_bytes = base.pix_bytes;
+    p.softmax = q.softmax;
     p.og_bytes = (int)((q.merged ? 32 : 18) * es);
     p.mg_bytes = (int)((q.merged ? 32 : 9) * es);
     if (pgi * p.og_bytes >= (1LL << 31))
@@ -944,7 +946,7 @@ int launch_tiled(const void *x, const void *off, const void *msk, const void *gy
 template <typename T, int CG, int THREADS>
 int launch_fwd_tiled(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
-    return launch_tiled<T, CG, THREADS, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0, g_opt.fwd_path == 2 || q.merged);
+    return launch_tiled<T, CG, THREADS, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0, g_opt.fwd_path == 2 || q.merged || q.softmax);
 }
 
 // The tiled kernel keeps Cg fp32 accumulators and 4*Cg input values per lane, so it is built
@@ -984,7 +986,7 @@ int dispatch_fwd_tiled(const void *x, const void *off, const void *msk, void *y,
                 if (make_tgeo(q, 256, kTiledFwd, &probe, CG, 1) == DCNV4_OK && probe.tiles_per_img == 1 &&
                     probe.R * probe.Q <= 16 * 64)
                     return launch_tiled<T, CG, 256, kTiledFwd>(x, off, msk, nullptr, y, nullptr, q, s, 0,
-                                                               g_opt.fwd_path == 2 || q.merged, 1, 3);
+                                                               g_opt.fwd_path == 2 || q.merged || q.softmax, 1, 3);
             }
             if (g_opt.fwd_threads == 512)
                 return launch_fwd_tiled<T, CG, 512>(x, off, msk, y, q, s);
@@ -1167,7 +1169,7 @@ int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const
 {
     // (maps of a few batches per image leave most of a ring workgroup idle: the rectangle kernels,
     // with several small workgroups per compute unit, are faster there -- measured at 14x14 and 7x7)
-    if (sizeof(T) == 2 && (g_opt.fwd_path == 3 || (g_opt.fwd_path == 0 && q.Ho * q.Wo >= 512))) {
+    if (sizeof(T) == 2 && !q.softmax && (g_opt.fwd_path == 3 || (g_opt.fwd_path == 0 && q.Ho * q.Wo >= 512))) {
         const int rc = dispatch_ring_fwd(x, off, msk, y, q, s);
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 3)
             return rc;
@@ -1179,7 +1181,7 @@ int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 2)
             return rc;
     }
-    if (q.merged)                            // (the direct kernels read the two tensors of the separate layout)
+    if (q.merged || q.softmax)               // (the direct kernels read two separate tensors and take m as given)
         return DCNV4_ERR_UNSUPPORTED;
     const int cpt = pick_fwd_cpt(q.Cg);
     switch (q.Cg) {
@@ -1249,7 +1251,7 @@ int launch_bwd_tiled(const void *x, const void *off, const void *msk, const void
     if constexpr (sizeof(T) == 4)
         gom_direct = !sliced && g_opt.gom_coop == 0;
     // (for fp16 there is no other backward, so the tile-size heuristic does not apply)
-    const bool any_size = g_opt.bwd_path == 2 || sizeof(T) == 2 || q.merged;
+    const bool any_size = g_opt.bwd_path == 2 || sizeof(T) == 2 || q.merged || q.softmax;
     // the grad_x pass: twelve waves keep the LDS busiest (measured)
     const int gxt = g_opt.gx_threads ? g_opt.gx_threads : 768;
     TiledLaunch l_gom, l_gx;
@@ -1300,6 +1302,7 @@ int fill_problem(Problem *q, int N, int H, int W, int G, int Cg, int kh, int kw,
     q->sh = sh; q->sw = sw; q->ph = ph; q->pw = pw; q->dh = dh; q->dw = dw;
     q->scale = scale; q->dtype = dtype;
     q->merged = 0;
+    q->softmax = 0;
     q->Ho = q->Wo = 0;
     if (H < 1 || W < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1)
         return DCNV4_ERR_SHAPE;
@@ -1331,7 +1334,7 @@ namespace {
 
 int forward_impl(const void *x, const void *offset, const void *mask, void *y, int N, int H, int W, int G, int Cg,
                  int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
-                 float offset_scale, int dtype, void *stream, bool merged)
+                 float offset_scale, int dtype, void *stream, bool merged, bool softmax = false)
 {
     const void *ptrs[4] = {x, offset, y, mask};
     for (int i = 0; i < (merged ? 3 : 4); ++i)
@@ -1345,6 +1348,7 @@ int forward_impl(const void *x, const void *offset, const void *mask, void *y, i
     rc = validate(q, kernel_h, kernel_w, ptrs, merged ? 3 : 4);
     if (rc)
         return rc;
+    q.softmax = softmax;
     if (merged) {
         // the mask values follow the 18 offsets of their (pixel, group) in the same buffer
         q.merged = 1;
@@ -1358,7 +1362,7 @@ int forward_impl(const void *x, const void *offset, const void *mask, void *y, i
 int backward_impl(const void *x, const void *offset, const void *mask, const void *grad_y, void *grad_x,
                   void *grad_offset, void *grad_mask, int N, int H, int W, int G, int Cg, int kernel_h,
                   int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
-                  float offset_scale, int dtype, void *stream, bool merged)
+                  float offset_scale, int dtype, void *stream, bool merged, bool softmax = false)
 {
     const void *ptrs[7] = {x, offset, grad_y, grad_x, grad_offset, mask, grad_mask};
     for (int i = 0; i < (merged ? 5 : 7); ++i)
@@ -1372,6 +1376,7 @@ int backward_impl(const void *x, const void *offset, const void *mask, const voi
     rc = validate(q, kernel_h, kernel_w, ptrs, merged ? 5 : 7);
     if (rc)
         return rc;
+    q.softmax = softmax;
     if (merged) {
         q.merged = 1;
         mask = (const char *)offset + 18 * esize(dtype);
@@ -1390,13 +1395,13 @@ int backward_impl(const void *x, const void *offset, const void *mask, const voi
             return launch_bwd_tiled<_Float16, 32>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         return DCNV4_ERR_UNSUPPORTED;
     }
-    if (g_opt.bwd_path != 1 || merged) {
+    if (g_opt.bwd_path != 1 || merged || softmax) {
         rc = DCNV4_ERR_UNSUPPORTED;
         if (Cg == 8)
             rc = launch_bwd_tiled<float, 8>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
         else if (Cg == 16 || Cg == 32 || Cg == 64)     // wider groups: 64-byte channel slices
             rc = launch_bwd_tiled<float, 16>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
-        if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.bwd_path == 2 || merged)
+        if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.bwd_path == 2 || merged || softmax)
             return rc;
     }
     const int cpt = pick_bwd_cpt(Cg);
@@ -1434,6 +1439,24 @@ int dcnv4_backward(const void *x, const void *offset, const void *mask, const vo
 {
     return backward_impl(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, N, H, W, G, Cg, kernel_h, kernel_w,
                          stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype, stream, false);
+}
+
+int dcnv4_forward_softmax(const void *x, const void *offset, const void *mask_logits, void *y, int N, int H, int W,
+                          int G, int Cg, int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w,
+                          int dil_h, int dil_w, float offset_scale, int dtype, void *stream)
+{
+    return forward_impl(x, offset, mask_logits, y, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w,
+                        dil_h, dil_w, offset_scale, dtype, stream, false, true);
+}
+
+int dcnv4_backward_softmax(const void *x, const void *offset, const void *mask_logits, const void *grad_y,
+                           void *grad_x, void *grad_offset, void *grad_mask_logits, int N, int H, int W, int G,
+                           int Cg, int kernel_h, int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w,
+                           int dil_h, int dil_w, float offset_scale, int dtype, void *stream)
+{
+    return backward_impl(x, offset, mask_logits, grad_y, grad_x, grad_offset, grad_mask_logits, N, H, W, G, Cg, kernel_h,
+                         kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype, stream, false,
+                         true);
 }
 
 int dcnv4_backward_merged(const void *x, const void *offset_mask, const void *grad_y, void *grad_x,

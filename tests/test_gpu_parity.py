@@ -136,6 +136,46 @@ def test_merged_buffer_forward_fp16_other_workloads(name):
     check_merged(CONFIGS[name], "f16", backward=False)
 
 
+# ------------------------------------------------------------------ softmax-normalised modulation (the DCNv3 form)
+def check_softmax(cfg, dtype, seed=0, backward=True):
+    t = make_inputs(cfg, dtype, seed=seed)
+    d = to_gpu(t, dtype)
+    y = dcn.dcnv4_forward_softmax(d["x"], d["offset"], d["mask"], **geo_kw(cfg))
+    torch.cuda.synchronize()
+    close(f"{cfg.name}/{dtype}/softmax/y", y.cpu().numpy(), oracle.forward_softmax(t["x"], t["offset"], t["mask"], **geo_kw(cfg)),
+          TOL[dtype])
+    if not backward:
+        return
+    out = (torch.full_like(d["x"], 7.0), torch.full_like(d["offset"], 7.0), torch.full_like(d["mask"], 7.0))
+    gx, go, gl = dcn.dcnv4_backward_softmax(d["x"], d["offset"], d["mask"], d["grad_y"], out=out, **geo_kw(cfg))
+    torch.cuda.synchronize()
+    rgx, rgo, rgl = oracle.backward_softmax(t["x"], t["offset"], t["mask"], t["grad_y"], **geo_kw(cfg))
+    close(f"{cfg.name}/{dtype}/softmax/grad_mask_logits", gl.cpu().numpy(), rgl, TOL[dtype])
+    close(f"{cfg.name}/{dtype}/softmax/grad_offset", go.cpu().numpy(), rgo, TOL[dtype])
+    close(f"{cfg.name}/{dtype}/softmax/grad_x", gx.cpu().numpy(), rgx, TOL[dtype])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_softmax_form_c1_and_c5_full_size(dtype):
+    check_softmax(CONFIGS["c1"], dtype)
+    check_softmax(CONFIGS["c5"], dtype)
+
+
+SOFTMAX = [Config("s_rag", N=3, H=13, W=11, C=48, G=3), Config("s_cg8", N=2, H=10, W=12, C=24, G=3),
+           Config("s_cg32", N=2, H=12, W=9, C=96, G=3), Config("s_s2", N=2, H=15, W=14, C=32, G=2, stride=2, sigma=3.0),
+           Config("s_big", N=2, H=24, W=30, C=32, G=2), Config("s_one", N=2, H=1, W=1, C=16, G=1),
+           Config("s_cg64", N=1, H=8, W=8, C=128, G=2)]
+
+
+@pytest.mark.parametrize("cfg", SOFTMAX, ids=[c.name for c in SOFTMAX])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("opts", [{}, {"halo": 1, "lds_kb": 48}], ids=["default", "small_tiles"])
+def test_softmax_form_geometries(cfg, dtype, opts):
+    for k, v in opts.items():
+        dcn.dcnv4_set_option(k, v)
+    check_softmax(cfg, dtype, seed=51, backward=not (dtype == "f16" and cfg.Cg == 64))
+
+
 # ------------------------------------------------------------------ the paper's own benchmark shapes
 PAPER_SHAPES = [n for n in CONFIGS if n.startswith("paper_")]
 

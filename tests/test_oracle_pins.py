@@ -302,3 +302,50 @@ def test_synthetic_inputs_are_reproducible_and_shaped():
     assert 0.08 < whole < 0.18
     c4 = CONFIGS["c4"]
     assert c4.sigma == 4.0 and c4.out_hw == (200, 336)
+
+
+# ------------------------------------------------------------------ the softmax-normalised (DCNv3) form
+def _small(seed=5):
+    rng = np.random.default_rng(seed)
+    x = rng.normal(size=(1, 6, 7, 8))
+    off = rng.normal(size=(1, 6, 7, 2, 9, 2)) * 1.5
+    logits = rng.normal(size=(1, 6, 7, 2, 9)) * 2.0
+    gy = rng.normal(size=(1, 6, 7, 8))
+    return x, off, logits, gy
+
+
+def test_softmax_form_uniform_logits_average_the_nine_samples():
+    x, off, logits, _ = _small()
+    y = oracle.forward_softmax(x, off, np.full_like(logits, 3.25))
+    np.testing.assert_allclose(y, oracle.forward(x, off, np.full_like(logits, 1.0 / 9.0)), rtol=1e-13, atol=1e-13)
+
+
+def test_softmax_form_ignores_a_constant_added_to_the_logits_and_picks_a_dominant_tap():
+    x, off, logits, _ = _small()
+    y = oracle.forward_softmax(x, off, logits)
+    shift = np.random.default_rng(1).normal(size=logits.shape[:4] + (1,)) * 7
+    np.testing.assert_allclose(oracle.forward_softmax(x, off, logits + shift), y, rtol=1e-12, atol=1e-12)
+    hot = np.zeros_like(logits)
+    hot[..., 4] = 60.0                                  # e^-60 of the weight is left for the other taps
+    one = np.zeros_like(logits)
+    one[..., 4] = 1.0
+    np.testing.assert_allclose(oracle.forward_softmax(x, off, hot), oracle.forward(x, off, one), rtol=0, atol=1e-12)
+
+
+def test_softmax_form_gradients():
+    x, off, logits, gy = _small()
+    gx, go, gl = oracle.backward_softmax(x, off, logits, gy)
+    # the nine logit gradients of a (pixel, group) sum to zero (softmax is shift invariant)
+    assert np.abs(gl.sum(axis=-1)).max() < 1e-12
+    # central differences w.r.t. a few logits, and w.r.t. x through the adjoint identity
+    f = lambda lg: float((oracle.forward_softmax(x, off, lg) * gy).sum())
+    rng = np.random.default_rng(2)
+    for _ in range(12):
+        idx = tuple(int(rng.integers(0, n)) for n in logits.shape)
+        d = np.zeros_like(logits)
+        d[idx] = 1e-5
+        assert (f(logits + d) - f(logits - d)) / 2e-5 == pytest.approx(gl[idx], rel=1e-6, abs=1e-8)
+    xp = rng.normal(size=x.shape)
+    assert float((oracle.forward_softmax(xp, off, logits) * gy).sum()) == pytest.approx(float((gx * xp).sum()), rel=1e-12)
+    # grad_offset is the plain operator's with the normalised m
+    np.testing.assert_allclose(go, oracle.backward(x, off, oracle.softmax_taps(logits), gy)[1], rtol=0, atol=0)
