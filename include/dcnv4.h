@@ -27,7 +27,9 @@
  * on `stream` (a hipStream_t, NULL = the default stream) and returns without
  * synchronising.  Outputs must not alias inputs.
  *
- * Supported: kernel 3x3; stride, dilation >= 1; pad >= 0; Cg in {8, 16, 32, 64};
+ * Supported: square windows of 3x3 (every entry point and kernel), 1x1 and 5x5 (dcnv4_forward in
+ * F32 and F16, dcnv4_backward in F32, through the direct kernels; 5x5 forward needs Cg >= 16; K = 1 or
+ * 25 replaces 9 in the layouts above); stride, dilation >= 1; pad >= 0; Cg in {8, 16, 32, 64};
  * dtype F32 or F16.  F16 is fp16 storage with fp32 positions and accumulation and one
  * round-to-nearest at the store; where the forward runs out of its ring of input rows
  * in LDS (fp16, Cg 16, maps of several hundred pixels) the four products m * corner

@@ -283,14 +283,15 @@ __device__ __forceinline__ Item decode_item(const Geo &p, int tile)
 // ------------------------------------------------------------------------------------------
 // Forward (Eq. 1-2): thread = (output pixel, group, run of CPT channels).
 // ------------------------------------------------------------------------------------------
-template <typename T, int CG, int CPT>
+template <typename T, int CG, int CPT, int KH = 3, int KW = 3>
 __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict__ x, const T *__restrict__ offset,
                                                              const T *__restrict__ mask, T *__restrict__ y, Geo p)
 {
     constexpr int TPG = CG / CPT;
+    constexpr int KT = KH * KW;                 // sampling points of the window
     constexpr int PGB = kThreads / TPG;
-    constexpr int OFF_CAP = PGB * 2 * kTaps * (int)sizeof(T) + 16;
-    constexpr int MSK_CAP = PGB * kTaps * (int)sizeof(T) + 16;
+    constexpr int OFF_CAP = PGB * 2 * KT * (int)sizeof(T) + 16;
+    constexpr int MSK_CAP = PGB * KT * (int)sizeof(T) + 16;
     __shared__ __attribute__((aligned(16))) char s_off[OFF_CAP];
     __shared__ __attribute__((aligned(16))) char s_msk[MSK_CAP];
 
@@ -300,16 +301,16 @@ __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict
     const Item it = decode_item<TPG>(p, tile);
 
     const long long pg_first = (long long)it.n * p.pgi + it.pg0;
-    const int d_off = stage_region<OFF_CAP, (int)sizeof(T)>(s_off, (const char *)offset, pg_first * (2 * kTaps * (int)sizeof(T)),
-                                            it.npg * 2 * kTaps * (int)sizeof(T));
-    const int d_msk = stage_region<MSK_CAP, (int)sizeof(T)>(s_msk, (const char *)mask, pg_first * (kTaps * (int)sizeof(T)),
-                                            it.npg * kTaps * (int)sizeof(T));
+    const int d_off = stage_region<OFF_CAP, (int)sizeof(T)>(s_off, (const char *)offset, pg_first * (2 * KT * (int)sizeof(T)),
+                                            it.npg * 2 * KT * (int)sizeof(T));
+    const int d_msk = stage_region<MSK_CAP, (int)sizeof(T)>(s_msk, (const char *)mask, pg_first * (KT * (int)sizeof(T)),
+                                            it.npg * KT * (int)sizeof(T));
     __syncthreads();
     if (!it.active)
         return;
 
-    const T *my_off = reinterpret_cast<const T *>(s_off + d_off) + it.pgl * 2 * kTaps;
-    const T *my_msk = reinterpret_cast<const T *>(s_msk + d_msk) + it.pgl * kTaps;
+    const T *my_off = reinterpret_cast<const T *>(s_off + d_off) + it.pgl * 2 * KT;
+    const T *my_msk = reinterpret_cast<const T *>(s_msk + d_msk) + it.pgl * KT;
     const rsrc_t rx = make_rsrc((const char *)x + (long long)it.n * p.x_img_bytes, (unsigned)p.x_img_bytes);
     const int chan_bytes = (it.g * CG + it.sub * CPT) * (int)sizeof(T);
     const int bh = it.oh * p.sh - p.ph, bw = it.ow * p.sw - p.pw;
@@ -320,10 +321,10 @@ __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict
         acc[c] = 0.f;
 
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
+    for (int j = 0; j < KW; ++j) {
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const int k = j * 3 + i;
+        for (int i = 0; i < KH; ++i) {
+            const int k = j * KH + i;
             const Tap t = tap_geometry((float)my_off[2 * k + 1], (float)my_off[2 * k], bh + i * p.dh, bw + j * p.dw,
                                        chan_bytes, p);
             Vec<T, CPT> v00, v01, v10, v11;
@@ -382,7 +383,7 @@ __device__ __forceinline__ float group_sum(float v)
     return v;
 }
 
-template <int CG, int CPT>
+template <int CG, int CPT, int KH = 3, int KW = 3>
 __global__ __launch_bounds__(kThreads) void dcnv4_bwd_kernel(const float *__restrict__ x,
                                                              const float *__restrict__ offset,
                                                              const float *__restrict__ mask,
@@ -393,9 +394,10 @@ __global__ __launch_bounds__(kThreads) void dcnv4_bwd_kernel(const float *__rest
 {
     typedef float T;
     constexpr int TPG = CG / CPT;
+    constexpr int KT = KH * KW;
     constexpr int PGB = kThreads / TPG;
-    constexpr int OFF_CAP = PGB * 2 * kTaps * (int)sizeof(T) + 16;
-    constexpr int MSK_CAP = PGB * kTaps * (int)sizeof(T) + 16;
+    constexpr int OFF_CAP = PGB * 2 * KT * (int)sizeof(T) + 16;
+    constexpr int MSK_CAP = PGB * KT * (int)sizeof(T) + 16;
     __shared__ __attribute__((aligned(16))) char s_off[OFF_CAP];
     __shared__ __attribute__((aligned(16))) char s_msk[MSK_CAP];
 
@@ -405,17 +407,17 @@ __global__ __launch_bounds__(kThreads) void dcnv4_bwd_kernel(const float *__rest
     const Item it = decode_item<TPG>(p, tile);
 
     const long long pg_first = (long long)it.n * p.pgi + it.pg0;
-    const int d_off = stage_region<OFF_CAP, (int)sizeof(T)>(s_off, (const char *)offset, pg_first * (2 * kTaps * (int)sizeof(T)),
-                                            it.npg * 2 * kTaps * (int)sizeof(T));
-    const int d_msk = stage_region<MSK_CAP, (int)sizeof(T)>(s_msk, (const char *)mask, pg_first * (kTaps * (int)sizeof(T)),
-                                            it.npg * kTaps * (int)sizeof(T));
+    const int d_off = stage_region<OFF_CAP, (int)sizeof(T)>(s_off, (const char *)offset, pg_first * (2 * KT * (int)sizeof(T)),
+                                            it.npg * 2 * KT * (int)sizeof(T));
+    const int d_msk = stage_region<MSK_CAP, (int)sizeof(T)>(s_msk, (const char *)mask, pg_first * (KT * (int)sizeof(T)),
+                                            it.npg * KT * (int)sizeof(T));
     __syncthreads();
 
     T *tile_off = reinterpret_cast<T *>(s_off + d_off);
     T *tile_msk = reinterpret_cast<T *>(s_msk + d_msk);
     if (it.active) {
-        T *my_off = tile_off + it.pgl * 2 * kTaps;
-        T *my_msk = tile_msk + it.pgl * kTaps;
+        T *my_off = tile_off + it.pgl * 2 * KT;
+        T *my_msk = tile_msk + it.pgl * KT;
         const rsrc_t rx = make_rsrc((const char *)x + (long long)it.n * p.x_img_bytes, (unsigned)p.x_img_bytes);
         const rsrc_t rgx = make_rsrc((char *)grad_x + (long long)it.n * p.x_img_bytes, (unsigned)p.x_img_bytes);
         const rsrc_t rgy =
@@ -427,10 +429,10 @@ __global__ __launch_bounds__(kThreads) void dcnv4_bwd_kernel(const float *__rest
         gy.load(rgy, it.pix * p.pix_bytes + chan_bytes);
 
 #pragma unroll
-        for (int j = 0; j < 3; ++j) {
+        for (int j = 0; j < KW; ++j) {
 #pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                const int k = j * 3 + i;
+            for (int i = 0; i < KH; ++i) {
+                const int k = j * KH + i;
                 const Tap t = tap_geometry(my_off[2 * k + 1], my_off[2 * k], bh + i * p.dh, bw + j * p.dw,
                                            chan_bytes, p);
                 Vec<T, CPT> v00, v01, v10, v11;
@@ -472,11 +474,11 @@ __global__ __launch_bounds__(kThreads) void dcnv4_bwd_kernel(const float *__rest
         }
     }
     __syncthreads();
-    float *go = grad_offset + pg_first * (2 * kTaps);
-    float *gm = grad_mask + pg_first * kTaps;
-    for (int e = threadIdx.x; e < it.npg * 2 * kTaps; e += kThreads)
+    float *go = grad_offset + pg_first * (2 * KT);
+    float *gm = grad_mask + pg_first * KT;
+    for (int e = threadIdx.x; e < it.npg * 2 * KT; e += kThreads)
         go[e] = tile_off[e];
-    for (int e = threadIdx.x; e < it.npg * kTaps; e += kThreads)
+    for (int e = threadIdx.x; e < it.npg * KT; e += kThreads)
         gm[e] = tile_msk[e];
 }
 
@@ -533,6 +535,7 @@ int esize(int dtype) { return dtype == DCNV4_F16 ? 2 : 4; }
 
 struct Problem {
     int N, H, W, G, Cg, Ho, Wo;
+    int kh, kw;     // window: 3x3 everywhere; 1x1 and 5x5 through the direct kernels only
     int sh, sw, ph, pw, dh, dw;
     float scale;
     int dtype;
@@ -550,7 +553,7 @@ int validate(const Problem &q, int kh, int kw, const void *const *ptrs, int nptr
         return DCNV4_ERR_SHAPE;
     if (q.Ho < 1 || q.Wo < 1)
         return DCNV4_ERR_SHAPE;
-    if (kh != 3 || kw != 3)
+    if (kh != kw || (kh != 1 && kh != 3 && kh != 5))
         return DCNV4_ERR_UNSUPPORTED;
     if (q.dtype != DCNV4_F32 && q.dtype != DCNV4_F16)
         return DCNV4_ERR_UNSUPPORTED;
@@ -574,9 +577,9 @@ int make_geo(const Problem &q, int tpg, Geo *out)
     p.H = q.H; p.W = q.W; p.Ho = q.Ho; p.Wo = q.Wo; p.G = q.G;
     p.sh = q.sh; p.sw = q.sw; p.ph = q.ph; p.pw = q.pw; p.dh = q.dh; p.dw = q.dw;
     p.scale = q.scale;
-    // window origin of any tap lies in [-pad, (out-1)*stride - pad + 2*dil]
-    const long long bh = (long long)(q.Ho - 1) * q.sh + 2LL * q.dh + q.ph;
-    const long long bw = (long long)(q.Wo - 1) * q.sw + 2LL * q.dw + q.pw;
+    // window origin of any tap lies in [-pad, (out-1)*stride - pad + (k-1)*dil]
+    const long long bh = (long long)(q.Ho - 1) * q.sh + (long long)(q.kh - 1) * q.dh + q.ph;
+    const long long bw = (long long)(q.Wo - 1) * q.sw + (long long)(q.kw - 1) * q.dw + q.pw;
     const long long reach = (q.H > q.W ? q.H : q.W) + (bh > bw ? bh : bw) + 4;
     if (reach >= (1 << 22))
         return DCNV4_ERR_UNSUPPORTED;
@@ -632,18 +635,40 @@ int pick_bwd_cpt(int Cg)
     return c;
 }
 
-template <typename T, int CG, int CPT>
+template <typename T, int CG, int CPT, int KS = 3>
 int launch_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
     Geo p;
     int rc = make_geo(q, CG / CPT, &p);
     if (rc)
         return rc;
-    hipLaunchKernelGGL((dcnv4_fwd_kernel<T, CG, CPT>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const T *)x,
+    hipLaunchKernelGGL((dcnv4_fwd_kernel<T, CG, CPT, KS, KS>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const T *)x,
                        (const T *)off, (const T *)msk, (T *)y, p);
-    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_fwd_kernel<%s, %d, %d>",
-             sizeof(T) == 2 ? "_Float16" : "float", CG, CPT);
+    if (KS == 3)
+        snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_fwd_kernel<%s, %d, %d>",
+                 sizeof(T) == 2 ? "_Float16" : "float", CG, CPT);
+    else
+        snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_fwd_kernel<%s, %d, %d, %d, %d>",
+                 sizeof(T) == 2 ? "_Float16" : "float", CG, CPT, KS, KS);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
+// Windows other than 3x3 (1x1, 5x5): the direct kernel, eight channels per lane.  A 5x5 window keeps
+// 75 values per (pixel, group) in the kernel's static LDS tiles, which fit for groups of 16 channels
+// or more (128 pairs per workgroup).
+template <typename T, int KS>
+int dispatch_fwd_window(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
+{
+    switch (q.Cg) {
+    case 8:
+        if constexpr (KS <= 3)
+            return launch_fwd<T, 8, 8, KS>(x, off, msk, y, q, s);
+        return DCNV4_ERR_UNSUPPORTED;
+    case 16: return launch_fwd<T, 16, 8, KS>(x, off, msk, y, q, s);
+    case 32: return launch_fwd<T, 32, 8, KS>(x, off, msk, y, q, s);
+    case 64: return launch_fwd<T, 64, 8, KS>(x, off, msk, y, q, s);
+    }
+    return DCNV4_ERR_UNSUPPORTED;
 }
 
 template <typename T, int CG>
@@ -1167,6 +1192,11 @@ int dispatch_ring_fwd(const void *x, const void *off, const void *msk, void *y, 
 template <typename T>
 int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
+    if (q.kh != 3) {
+        if (q.merged || q.softmax || g_opt.fwd_path >= 2)
+            return DCNV4_ERR_UNSUPPORTED;
+        return q.kh == 1 ? dispatch_fwd_window<T, 1>(x, off, msk, y, q, s) : dispatch_fwd_window<T, 5>(x, off, msk, y, q, s);
+    }
     // (maps of a few batches per image leave most of a ring workgroup idle: the rectangle kernels,
     // with several small workgroups per compute unit, are faster there -- measured at 14x14 and 7x7)
     if (sizeof(T) == 2 && !q.softmax && (g_opt.fwd_path == 3 || (g_opt.fwd_path == 0 && q.Ho * q.Wo >= 512))) {
@@ -1193,7 +1223,7 @@ int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const
     return DCNV4_ERR_UNSUPPORTED;
 }
 
-template <int CG, int CPT>
+template <int CG, int CPT, int KS = 3>
 int launch_bwd(const void *x, const void *off, const void *msk, const void *gy, void *gx, void *go, void *gm,
                const Problem &q, hipStream_t s)
 {
@@ -1205,10 +1235,13 @@ int launch_bwd(const void *x, const void *off, const void *msk, const void *gy, 
     long long zb = (zbytes / 16 + kThreads - 1) / kThreads;
     if (zb > 8192) zb = 8192;
     hipLaunchKernelGGL(dcnv4_zero_kernel, dim3((unsigned)zb), dim3(kThreads), 0, s, (u32x4 *)gx, zbytes);
-    hipLaunchKernelGGL((dcnv4_bwd_kernel<CG, CPT>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const float *)x,
+    hipLaunchKernelGGL((dcnv4_bwd_kernel<CG, CPT, KS, KS>), dim3(grid_of(p)), dim3(kThreads), 0, s, (const float *)x,
                        (const float *)off, (const float *)msk, (const float *)gy, (float *)gx, (float *)go,
                        (float *)gm, p);
-    snprintf(g_last_kernel[1], sizeof(g_last_kernel[1]), "dcnv4_bwd_kernel<%d, %d>", CG, CPT);
+    if (KS == 3)
+        snprintf(g_last_kernel[1], sizeof(g_last_kernel[1]), "dcnv4_bwd_kernel<%d, %d>", CG, CPT);
+    else
+        snprintf(g_last_kernel[1], sizeof(g_last_kernel[1]), "dcnv4_bwd_kernel<%d, %d, %d, %d>", CG, CPT, KS, KS);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
 }
 
@@ -1299,6 +1332,7 @@ int fill_problem(Problem *q, int N, int H, int W, int G, int Cg, int kh, int kw,
                  int dh, int dw, float scale, int dtype)
 {
     q->N = N; q->H = H; q->W = W; q->G = G; q->Cg = Cg;
+    q->kh = kh; q->kw = kw;
     q->sh = sh; q->sw = sw; q->ph = ph; q->pw = pw; q->dh = dh; q->dw = dw;
     q->scale = scale; q->dtype = dtype;
     q->merged = 0;
@@ -1383,6 +1417,27 @@ int backward_impl(const void *x, const void *offset, const void *mask, const voi
         grad_mask = (char *)grad_offset + 18 * esize(dtype);
     }
     hipStream_t s = (hipStream_t)stream;
+    if (kernel_h != 3) {
+        // 1x1 and 5x5 windows: the direct fp32 kernel, one channel per lane (two for groups of 64)
+        if (merged || softmax || dtype != DCNV4_F32 || g_opt.bwd_path == 2)
+            return DCNV4_ERR_UNSUPPORTED;
+        if (kernel_h == 1) {
+            switch (Cg) {
+            case 8: return launch_bwd<8, 1, 1>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            case 16: return launch_bwd<16, 1, 1>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            case 32: return launch_bwd<32, 1, 1>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            case 64: return launch_bwd<64, 2, 1>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            }
+        } else {
+            switch (Cg) {
+            case 8: return launch_bwd<8, 1, 5>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            case 16: return launch_bwd<16, 1, 5>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            case 32: return launch_bwd<32, 1, 5>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            case 64: return launch_bwd<64, 2, 5>(x, offset, mask, grad_y, grad_x, grad_offset, grad_mask, q, s);
+            }
+        }
+        return DCNV4_ERR_UNSUPPORTED;
+    }
     if (dtype == DCNV4_F16) {
         // fp16 storage, fp32 arithmetic; only the LDS-staged kernels exist for it (Cg 8, 16 or 32)
         if (g_opt.bwd_path == 1)

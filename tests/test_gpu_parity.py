@@ -176,6 +176,22 @@ def test_softmax_form_geometries(cfg, dtype, opts):
     check_softmax(cfg, dtype, seed=51, backward=not (dtype == "f16" and cfg.Cg == 64))
 
 
+# ------------------------------------------------------------------ windows other than 3x3
+WINDOWS = [Config("k1", N=2, H=9, W=11, C=48, G=3, kernel=1, pad=0), Config("k1_cg8", N=1, H=7, W=7, C=16, G=2, kernel=1, pad=0),
+           Config("k1_s2", N=2, H=12, W=10, C=64, G=2, kernel=1, pad=1, stride=2),
+           Config("k5", N=2, H=11, W=13, C=32, G=2, kernel=5, pad=2), Config("k5_cg64", N=1, H=8, W=9, C=128, G=2, kernel=5, pad=2),
+           Config("k5_d2", N=1, H=17, W=15, C=64, G=2, kernel=5, pad=4, dilation=2, stride=2, sigma=3.0)]
+
+
+@pytest.mark.parametrize("cfg", WINDOWS, ids=[c.name for c in WINDOWS])
+def test_windows_of_1x1_and_5x5(cfg):
+    """K = 1 and K = 25 sampling points (tap k = j*kernel + i as for 3x3) through the direct kernels."""
+    check_forward(cfg, "f32", seed=61)
+    check_forward(cfg, "f16", seed=61)
+    check_backward(cfg, seed=62)
+    assert dcn.dcnv4_last_kernel_name(1).startswith("dcnv4_bwd_kernel<")
+
+
 # ------------------------------------------------------------------ the paper's own benchmark shapes
 PAPER_SHAPES = [n for n in CONFIGS if n.startswith("paper_")]
 
@@ -460,9 +476,9 @@ def test_gpu_call_with_bad_arguments_returns_error_and_writes_nothing():
     cfg = Config("bad", N=1, H=8, W=8, C=32, G=2)
     d = to_gpu(make_inputs(cfg, "f32", seed=11), "f32")
     y = torch.full((1, 8, 8, 32), 5.0, device="cuda")
-    with pytest.raises(dcn.Dcnv4Error) as e:                                 # 5x5 window: outside the supported set
-        dcn.dcnv4_forward(d["x"], d["x"].new_zeros((1, 6, 6, 2, 25, 2)), d["x"].new_zeros((1, 6, 6, 2, 25)),
-                          kernel=5, out=y[:, :6, :6].contiguous())
+    with pytest.raises(dcn.Dcnv4Error) as e:                                 # 7x7 window: outside the supported set
+        dcn.dcnv4_forward(d["x"], d["x"].new_zeros((1, 4, 4, 2, 49, 2)), d["x"].new_zeros((1, 4, 4, 2, 49)),
+                          kernel=7, out=y[:, :4, :4].contiguous())
     assert e.value.status == 3
     with pytest.raises(dcn.Dcnv4Error):
         wide = to_gpu(make_inputs(Config("wide", N=1, H=8, W=8, C=128, G=2), "f16", seed=11), "f16")
