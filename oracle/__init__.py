@@ -152,3 +152,49 @@ def backward_softmax(x, offset, mask_logits, grad_y, **kw):
     gx, go, gm = backward(x, offset, m, grad_y, **kw)
     gl = m * (gm - (m * gm).sum(axis=-1, keepdims=True))
     return gx, go, gl
+
+
+def linear(x, w, b=None):
+    """A linear layer over the channel axis (a 1x1 point-wise convolution, Sec. 3.1):
+    y[..., o] = sum_c x[..., c] * w[o, c] + b[o], in double precision."""
+    y = _f64(x) @ _f64(w).T
+    if b is not None:
+        y = y + _f64(b)
+    return y
+
+
+def _stored(a, storage):
+    """What a layer hands to the next one: the double-precision value, or that value rounded once to
+    the type the tensors are stored in (the half-precision module keeps every tensor in fp16, Sec. 3.2)."""
+    return a if storage is None else a.astype(storage).astype(np.float64)
+
+
+def module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_out=None, storage=None, **kw):
+    """The DCNv4 module (Sec. 3.1 last paragraph of the DCNv3 review, Sec. 3.2 "Micro design", and the
+    two variants of the module-level benchmark in the appendix), no depthwise convolution:
+        value = x W_in^T + b_in                      (left out in the lightweight variant: value = x)
+        om    = x W_om^T + b_om                      ONE linear layer: per group 2K offsets (tap-major,
+                                                     width then height), then the K modulation scalars
+        y_op  = Eq. 1-2 on (value, offsets, scalars) no softmax
+        y     = y_op W_out^T + b_out                 (left out in the lightweight variant)
+    x [N,H,W,C]; w_om [G*3K, C]; w_in, w_out [C, C] (both given, or both None).  The window must keep
+    the map's size (stride 1, pad = dilation*(kernel-1)/2): the layer predicts one set of offsets per
+    input pixel.  `storage` (None, np.float16 or np.float32): the type the tensors between the layers are
+    rounded to."""
+    if (w_in is None) != (w_out is None):
+        raise ValueError("input and output projections come together")
+    x = _f64(x)
+    kh, kw_ = _pair(kw.get("kernel", 3))
+    K = kh * kw_
+    N, H, W, C = x.shape
+    if _f64(w_om).shape != (G * 3 * K, C):
+        raise ValueError(f"w_om of shape {np.shape(w_om)}, expected {(G * 3 * K, C)}")
+    value = x if w_in is None else _stored(linear(x, w_in, b_in), storage)
+    om = _stored(linear(x, w_om, b_om), storage).reshape(N, H, W, G, 3 * K)
+    offset, mask = split_merged(om, kw.get("kernel", 3))
+    y = forward(value, offset, mask, **kw)
+    if y.shape[1:3] != (H, W):
+        raise ValueError("the module needs a window that keeps the map's size")
+    if w_out is None:
+        return y
+    return linear(_stored(y, storage), w_out, b_out)

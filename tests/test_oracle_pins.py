@@ -349,3 +349,106 @@ def test_softmax_form_gradients():
     assert float((oracle.forward_softmax(xp, off, logits) * gy).sum()) == pytest.approx(float((gx * xp).sum()), rel=1e-12)
     # grad_offset is the plain operator's with the normalised m
     np.testing.assert_allclose(go, oracle.backward(x, off, oracle.softmax_taps(logits), gy)[1], rtol=0, atol=0)
+
+
+# ------------------------------------------------------------------ the module around the operator
+def box3(a):
+    """Sum over the zero-padded 3x3 neighbourhood of every pixel of a [N,H,W,C] map (slices, no library)."""
+    N, H, W, C = a.shape
+    p = np.zeros((N, H + 2, W + 2, C))
+    p[:, 1:-1, 1:-1] = a
+    return sum(p[:, i:i + H, j:j + W] for i in range(3) for j in range(3))
+
+
+def om_bias(G, offsets, masks):
+    """Bias of the merged layer that makes every pixel predict the given 9 (dx, dy) pairs and 9 scalars."""
+    per_group = np.concatenate([np.asarray(offsets, dtype=np.float64).reshape(18), np.asarray(masks, dtype=np.float64)])
+    return np.tile(per_group, G)
+
+
+def test_module_with_identity_projections_and_a_centre_tap_returns_its_input():
+    rng = np.random.default_rng(21)
+    G, Cg = 2, 4
+    C = G * Cg
+    x = rng.standard_normal((2, 5, 6, C))
+    centre = np.zeros(9)
+    centre[4] = 1.0                                                 # k = j*3 + i = 4: the window's middle
+    b_om = om_bias(G, np.zeros((9, 2)), centre)
+    w_om = np.zeros((G * 27, C))
+    np.testing.assert_array_equal(oracle.module_forward(x, w_om, b_om, G), x)                 # lightweight
+    eye = np.eye(C)
+    np.testing.assert_array_equal(oracle.module_forward(x, w_om, b_om, G, w_in=eye, b_in=np.zeros(C), w_out=eye,
+                                                        b_out=np.zeros(C)), x)
+
+
+def test_module_with_constant_offsets_is_projection_box_filter_projection():
+    """Zero offsets and all scalars 1/9: the operator is the 3x3 mean with zero padding, which commutes with the
+    point-wise layers except for the input bias (a padded value is 0, not b_in): with cnt = number of
+    in-image neighbours, y = ((box(x) W_in^T + cnt b_in) / 9) W_out^T + b_out."""
+    rng = np.random.default_rng(22)
+    G, Cg = 3, 4
+    C = G * Cg
+    x = rng.standard_normal((2, 6, 5, C))
+    w_in, w_out = rng.standard_normal((C, C)), rng.standard_normal((C, C))
+    b_in, b_out = rng.standard_normal(C), rng.standard_normal(C)
+    b_om = om_bias(G, np.zeros((9, 2)), np.full(9, 1.0 / 9.0))
+    y = oracle.module_forward(x, np.zeros((G * 27, C)), b_om, G, w_in=w_in, b_in=b_in, w_out=w_out, b_out=b_out)
+    cnt = box3(np.ones((2, 6, 5, 1)))
+    want = ((box3(x) @ w_in.T + cnt * b_in) / 9.0) @ w_out.T + b_out
+    np.testing.assert_allclose(y, want, rtol=1e-12, atol=1e-12)
+    assert not np.allclose(y, ((box3(x) @ w_in + cnt * b_in) / 9.0) @ w_out + b_out)         # transposed weights differ
+
+
+def test_module_offsets_and_scalars_come_from_the_input_through_the_merged_layer():
+    """Channel 0 of group g's input steers that group's taps: dx_k = a_g * x0, dy_k = b_g * x0, m_k = c_gk * x0
+    (rows of w_om with a single entry).  On an affine image f = al*h + be*w + ga bilinear sampling is
+    exact inside the image, so y_g(p) = x0 * sum_k c_gk * f(p + p_k + x0 * (b_g, a_g)) in closed form."""
+    rng = np.random.default_rng(23)
+    G, Cg, H, W = 2, 3, 12, 13
+    C = G * Cg
+    hh, ww = np.meshgrid(np.arange(H, dtype=np.float64), np.arange(W, dtype=np.float64), indexing="ij")
+    x = np.zeros((1, H, W, C))
+    al, be, ga = rng.standard_normal(C), rng.standard_normal(C), rng.standard_normal(C)
+    x[0] = al * hh[..., None] + be * ww[..., None] + ga
+    steer = rng.uniform(0.2, 1.0, (H, W))                            # displacements stay below 2 pixels
+    a, b = np.array([1.3, -0.7]), np.array([-1.9, 0.6])
+    c = rng.standard_normal((G, 9))
+    w_om = np.zeros((G * 27, C))
+    for g in range(G):
+        x[0, :, :, g * Cg] = steer                                   # (so channel g*Cg is not affine; excluded below)
+        for k in range(9):
+            w_om[g * 27 + 2 * k, g * Cg] = a[g]                      # dx of tap k
+            w_om[g * 27 + 2 * k + 1, g * Cg] = b[g]                  # dy of tap k
+            w_om[g * 27 + 18 + k, g * Cg] = c[g, k]
+    y = oracle.module_forward(x, w_om, np.zeros(G * 27), G)
+    inner = (slice(3, H - 3), slice(3, W - 3))
+    for g in range(G):
+        for ch in range(g * Cg + 1, (g + 1) * Cg):
+            want = np.zeros((H, W))
+            for k in range(9):
+                i, j = k % 3, k // 3                                 # height index fast, width index slow
+                f = al[ch] * (hh + i - 1 + b[g] * steer) + be[ch] * (ww + j - 1 + a[g] * steer) + ga[ch]
+                want += c[g, k] * steer * f
+            np.testing.assert_allclose(y[0, :, :, ch][inner], want[inner], rtol=1e-10, atol=1e-10)
+
+
+def test_module_storage_rounding_and_argument_checks():
+    rng = np.random.default_rng(24)
+    G, Cg = 2, 4
+    C = G * Cg
+    x = rng.standard_normal((1, 6, 6, C)).astype(np.float16)
+    w_om, b_om = 0.3 * rng.standard_normal((G * 27, C)), rng.standard_normal(G * 27)
+    w_in, w_out = rng.standard_normal((C, C)), rng.standard_normal((C, C))
+    exact = oracle.module_forward(x, w_om, b_om, G, w_in=w_in, b_in=None, w_out=w_out, b_out=None)
+    half = oracle.module_forward(x, w_om, b_om, G, w_in=w_in, b_in=None, w_out=w_out, b_out=None, storage=np.float16)
+    assert 0 < np.abs(exact - half).max() < 0.2                      # rounded intermediates: close, not equal
+    single = oracle.module_forward(x, w_om, b_om, G, w_in=w_in, b_in=None, w_out=w_out, b_out=None, storage=np.float32)
+    assert np.abs(exact - single).max() < 1e-4
+    with pytest.raises(ValueError):
+        oracle.module_forward(x, w_om[:-1], b_om, G)
+    with pytest.raises(ValueError):
+        oracle.module_forward(x, w_om, b_om, G, w_in=w_in)
+    with pytest.raises(ValueError):
+        oracle.module_forward(x, w_om, b_om, G, pad=0)               # a window that shrinks the map
+    np.testing.assert_array_equal(oracle.linear(np.array([[1.0, 2.0]]), np.array([[3.0, 4.0], [5.0, 6.0], [7.0, 8.0]]),
+                                                np.array([0.5, 0.0, -1.0])), [[11.5, 17.0, 22.0]])
