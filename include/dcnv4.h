@@ -139,6 +139,43 @@ int dcnv4_backward_softmax(const void *x, const void *offset, const void *mask_l
                            int pad_h, int pad_w, int dil_h, int dil_w,
                            float offset_scale, int dtype, void *stream);
 
+/* A linear layer over the channel axis -- the 1x1 point-wise convolution that Sec. 3.1 puts before and
+ * after the operator, and the layer of Sec. 3.2 "Micro design" that predicts offsets and modulation
+ * scalars:  y[p][o] = sum_k x[p][k] * w[o][k] + b[o].
+ * Device pointers, dense row-major: x [P][K], w [Nout][K], b [Nout] or NULL (no bias), y [P][Nout];
+ * x, w and y 16-byte aligned.  On the matrix cores with fp32 accumulation; y is rounded once in F16.
+ * Needs K * element size a multiple of 32 bytes, Nout a multiple of 32, and every tensor below 2 GiB
+ * (else DCNV4_ERR_UNSUPPORTED).  Allocates nothing; enqueues on `stream`. */
+int dcnv4_linear(const void *x, const void *w, const void *b, void *y,
+                 long long P, int K, int Nout, int dtype, void *stream);
+
+/* Forward of the DCNv4 module (Sec. 3.2 "Micro design"; the two variants of the module-level
+ * benchmark of the appendix), without the optional depthwise convolution:
+ *     value = x W_in^T + b_in          (w_in == w_out == NULL: the "lightweight" variant, value = x)
+ *     om    = x W_om^T + b_om          ONE layer for offsets and scalars, in the merged layout above:
+ *                                      w_om [G*32][C], b_om [G*32]; row g*32 + e produces entry e of
+ *                                      group g (0..17 offsets, 18..26 scalars, 27..31 ignored)
+ *     y_op  = dcnv4_forward_merged(value, om)
+ *     y     = y_op W_out^T + b_out     (left out in the lightweight variant: y = y_op)
+ * x, y [N,H,W,C], C = G*Cg; w_in, w_out [C][C]; biases may be NULL.  The window must be 3x3 and keep
+ * the map's size (stride 1, pad = dilation), C * element size a multiple of 32 bytes.  `workspace`:
+ * device memory of at least dcnv4_module_workspace_bytes() bytes, 16-byte aligned, owned by the caller;
+ * it holds om, value and y_op during the call and may be reused afterwards.  The value projection
+ * and the merged layer run as one kernel that reads x once.  Tensors between the layers are stored in
+ * `dtype`.  On an error y is untouched (the workspace may have been written). */
+int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in,
+                         const void *w_om, const void *b_om,
+                         const void *w_out, const void *b_out,
+                         void *workspace, long long workspace_bytes, void *y,
+                         int N, int H, int W, int G, int Cg,
+                         int kernel_h, int kernel_w, int stride_h, int stride_w,
+                         int pad_h, int pad_w, int dil_h, int dil_w,
+                         float offset_scale, int dtype, void *stream);
+
+/* Bytes of workspace dcnv4_module_forward needs (lightweight != 0: without the two projections);
+ * -1 for a bad argument.  Host-only helper. */
+long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int dtype, int lightweight);
+
 /* Bytes the ideal memory-access model of Sec. 3.2 ("2HWC + 27HWG", every value touched
  * once) assigns to one forward call: x + offset + mask + y.  Host-only helper. */
 long long dcnv4_forward_algorithmic_bytes(int N, int H, int W, int G, int Cg,

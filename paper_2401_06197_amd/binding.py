@@ -17,6 +17,7 @@ DCNV4_OK = 0
 EXPORTS = (
     "dcnv4_output_hw", "dcnv4_forward", "dcnv4_backward", "dcnv4_forward_merged", "dcnv4_backward_merged",
     "dcnv4_forward_softmax", "dcnv4_backward_softmax",
+    "dcnv4_linear", "dcnv4_module_forward", "dcnv4_module_workspace_bytes",
     "dcnv4_forward_algorithmic_bytes", "dcnv4_backward_algorithmic_bytes",
     "dcnv4_forward_merged_algorithmic_bytes", "dcnv4_backward_merged_algorithmic_bytes",
     "dcnv4_set_option", "dcnv4_last_kernel_name", "dcnv4_status_string",
@@ -62,6 +63,12 @@ def load_library():
               lib.dcnv4_forward_merged_algorithmic_bytes, lib.dcnv4_backward_merged_algorithmic_bytes):
         f.argtypes = [ci] * 8
         f.restype = ctypes.c_longlong
+    lib.dcnv4_linear.argtypes = [vp] * 4 + [ctypes.c_longlong, ci, ci, ci, vp]
+    lib.dcnv4_linear.restype = ci
+    lib.dcnv4_module_forward.argtypes = [vp] * 8 + [ctypes.c_longlong, vp] + geo
+    lib.dcnv4_module_forward.restype = ci
+    lib.dcnv4_module_workspace_bytes.argtypes = [ci] * 7
+    lib.dcnv4_module_workspace_bytes.restype = ctypes.c_longlong
     lib.dcnv4_set_option.argtypes = [ctypes.c_char_p, ci]
     lib.dcnv4_set_option.restype = ci
     lib.dcnv4_last_kernel_name.argtypes = [ci]
@@ -286,3 +293,80 @@ def dcnv4_backward_merged(x, offset_mask, grad_y, kernel=3, stride=1, pad=1, dil
     if rc:
         raise Dcnv4Error(rc, "dcnv4_backward_merged")
     return gx, gom
+
+
+def dcnv4_linear(x, w, b=None, out=None, stream=None, prepare_only=False):
+    """y[..., o] = sum_k x[..., k] * w[o, k] + b[o]: a linear layer over the last axis of x (a 1x1
+    point-wise convolution of an NHWC map), on the matrix cores."""
+    import torch
+    if x.dim() < 2 or w.dim() != 2 or w.shape[1] != x.shape[-1] or (b is not None and tuple(b.shape) != (w.shape[0],)):
+        raise ValueError("dcnv4: expected x [..., K], w [Nout, K], b [Nout]")
+    for name, t in (("x", x), ("w", w)) + ((("b", b),) if b is not None else ()):
+        _check(name, t, x)
+    yshape = tuple(x.shape[:-1]) + (w.shape[0],)
+    if out is None:
+        out = torch.empty(yshape, dtype=x.dtype, device=x.device)
+    else:
+        _check("out", out, x)
+        if tuple(out.shape) != yshape:
+            raise ValueError("dcnv4: out has the wrong shape")
+    P = x.numel() // x.shape[-1]
+    args = (x.data_ptr(), w.data_ptr(), b.data_ptr() if b is not None else None, out.data_ptr(), P, x.shape[-1],
+            w.shape[0], _dtype_code(x), _stream_ptr(stream, x.device))
+    if prepare_only:
+        return args
+    with torch.cuda.device(x.device):
+        rc = load_library().dcnv4_linear(*args)
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_linear")
+    return out
+
+
+def dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, lightweight):
+    return int(load_library().dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, int(bool(lightweight))))
+
+
+def dcnv4_module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_out=None, kernel=3, stride=1, pad=1,
+                         dilation=1, offset_scale=1.0, workspace=None, out=None, stream=None, prepare_only=False):
+    """Forward of the DCNv4 module: (value projection,) ONE linear layer for offsets and modulation
+    scalars, the operator, (output projection).  w_om [G*32, C] / b_om [G*32] in the merged layout
+    (row g*32 + e: entry e of group g; 0..17 offsets, 18..26 scalars, 27..31 ignored); w_in, w_out
+    [C, C] or both None (the lightweight variant)."""
+    import torch
+    if x.dim() != 4 or x.shape[3] % G:
+        raise ValueError("dcnv4: expected x [N,H,W,C] with C a multiple of G")
+    N, H, W, C = x.shape
+    (kh, kw), (sh, sw), (ph, pw), (dh, dw) = map(_pair, (kernel, stride, pad, dilation))
+    if (w_in is None) != (w_out is None):
+        raise ValueError("dcnv4: the input and output projections come together")
+    shapes = [("w_om", w_om, (G * 32, C)), ("b_om", b_om, (G * 32,)), ("w_in", w_in, (C, C)), ("b_in", b_in, (C,)),
+              ("w_out", w_out, (C, C)), ("b_out", b_out, (C,))]
+    for name, t, shape in shapes:
+        if t is not None:
+            _check(name, t, x)
+            if tuple(t.shape) != shape:
+                raise ValueError(f"dcnv4: {name} must have shape {shape}")
+    _check("x", x, x)
+    light = w_in is None
+    need = dcnv4_module_workspace_bytes(N, H, W, G, C // G, _dtype_code(x), light)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    elif not workspace.is_cuda or workspace.device != x.device or not workspace.is_contiguous():
+        raise ValueError("dcnv4: workspace must be a contiguous tensor on x's device")
+    if out is None:
+        out = torch.empty_like(x)
+    else:
+        _check("out", out, x)
+        if out.shape != x.shape:
+            raise ValueError("dcnv4: out has the wrong shape")
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    args = (x.data_ptr(), ptr(w_in), ptr(b_in), w_om.data_ptr(), ptr(b_om), ptr(w_out), ptr(b_out), workspace.data_ptr(),
+            workspace.numel() * workspace.element_size(), out.data_ptr(), N, H, W, G, C // G, kh, kw, sh, sw, ph, pw,
+            dh, dw, float(offset_scale), _dtype_code(x), _stream_ptr(stream, x.device))
+    if prepare_only:
+        return args
+    with torch.cuda.device(x.device):
+        rc = load_library().dcnv4_module_forward(*args)
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_module_forward")
+    return out

@@ -353,6 +353,7 @@ __global__ __launch_bounds__(kThreads) void dcnv4_fwd_kernel(const T *__restrict
 
 #include "dcnv4_tiled.inc"
 #include "dcnv4_ring.inc"
+#include "dcnv4_linear.inc"
 
 // ------------------------------------------------------------------------------------------
 // Backward (chain rule on Eq. 1), fp32, in one pass with grad_x added straight to memory; used
@@ -1469,6 +1470,59 @@ int backward_impl(const void *x, const void *offset, const void *mask, const voi
     return DCNV4_ERR_UNSUPPORTED;
 }
 
+// ---- the module's linear layers ----------------------------------------------------------------
+// One layer of the linear kernel's work list, checked: K * element size a multiple of 32 bytes (one
+// MFMA group), nout a multiple of 32 (one MFMA block), 32-bit byte offsets inside every tensor.
+int add_linear_segment(LinGeo *g, long long P, int K, int dtype, const void *w, const void *b, void *y, int nout)
+{
+    if (!w || !y)
+        return DCNV4_ERR_NULL;
+    if (nout < 1)
+        return DCNV4_ERR_SHAPE;
+    const long long es = esize(dtype);
+    if (nout % 32 || (long long)nout * K * es >= (1LL << 31) || P * nout * es >= (1LL << 31) || g->nseg >= kLinMaxSeg)
+        return DCNV4_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(w) & 15u) || (reinterpret_cast<uintptr_t>(y) & 15u) ||
+        (reinterpret_cast<uintptr_t>(b) & (uintptr_t)(es - 1)))
+        return DCNV4_ERR_ALIGN;
+    LinSeg &sg = g->seg[g->nseg++];
+    sg.w = w; sg.b = b; sg.y = y; sg.nout = nout;
+    sg.nblocks = (nout + kLinBlock - 1) / kLinBlock;
+    return DCNV4_OK;
+}
+
+int begin_linear(LinGeo *g, const void *x, long long P, int K, int dtype)
+{
+    memset(g, 0, sizeof(*g));
+    if (!x)
+        return DCNV4_ERR_NULL;
+    if (P < 1 || K < 1)
+        return DCNV4_ERR_SHAPE;
+    if (dtype != DCNV4_F32 && dtype != DCNV4_F16)
+        return DCNV4_ERR_UNSUPPORTED;
+    const long long kbytes = (long long)K * esize(dtype);
+    if (kbytes % 32 || P * kbytes >= (1LL << 31))
+        return DCNV4_ERR_UNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(x) & 15u)
+        return DCNV4_ERR_ALIGN;
+    g->P = (int)P;
+    g->kbytes = (int)kbytes;
+    g->nchunks = (int)((kbytes + kLinChunk - 1) / kLinChunk);
+    return DCNV4_OK;
+}
+
+int launch_linear(const void *x, const LinGeo &g, int dtype, hipStream_t s)
+{
+    const unsigned grid = (unsigned)((g.P + kLinPixels - 1) / kLinPixels);
+    if (dtype == DCNV4_F16)
+        hipLaunchKernelGGL(dcnv4_linear_kernel<_Float16>, dim3(grid), dim3(256), 0, s, (const _Float16 *)x, g);
+    else
+        hipLaunchKernelGGL(dcnv4_linear_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)x, g);
+    return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
 }  // namespace
 
 int dcnv4_forward(const void *x, const void *offset, const void *mask, void *y, int N, int H, int W, int G, int Cg,
@@ -1549,6 +1603,83 @@ long long dcnv4_backward_merged_algorithmic_bytes(int N, int H, int W, int G, in
     const long long es = esize(dtype), C = (long long)G * Cg;
     const long long P = (long long)N * H_out * W_out;
     return es * (2 * (long long)N * H * W * C + P * C + 2 * P * G * 32);
+}
+
+int dcnv4_linear(const void *x, const void *w, const void *b, void *y, long long P, int K, int Nout, int dtype,
+                 void *stream)
+{
+    LinGeo g;
+    int rc = begin_linear(&g, x, P, K, dtype);
+    if (rc)
+        return rc;
+    rc = add_linear_segment(&g, P, K, dtype, w, b, y, Nout);
+    if (rc)
+        return rc;
+    return launch_linear(x, g, dtype, (hipStream_t)stream);
+}
+
+long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int dtype, int lightweight)
+{
+    if (N < 1 || H < 1 || W < 1 || G < 1 || Cg < 1 || (dtype != DCNV4_F32 && dtype != DCNV4_F16))
+        return -1;
+    const long long P = (long long)N * H * W, es = esize(dtype), C = (long long)G * Cg;
+    const long long om = (long long)align256((size_t)(P * G * 32 * es)), act = (long long)align256((size_t)(P * C * es));
+    return lightweight ? om : om + 2 * act;
+}
+
+int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in, const void *w_om, const void *b_om,
+                         const void *w_out, const void *b_out, void *workspace, long long workspace_bytes, void *y,
+                         int N, int H, int W, int G, int Cg, int kernel_h, int kernel_w, int stride_h, int stride_w,
+                         int pad_h, int pad_w, int dil_h, int dil_w, float offset_scale, int dtype, void *stream)
+{
+    if (!x || !w_om || !workspace || !y)
+        return DCNV4_ERR_NULL;
+    if ((w_in == nullptr) != (w_out == nullptr))        // the two projections come together (or not at all)
+        return DCNV4_ERR_NULL;
+    const bool light = w_in == nullptr;
+    Problem q;
+    int rc = fill_problem(&q, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                          offset_scale, dtype);
+    if (rc)
+        return rc;
+    const void *ptrs[3] = {x, workspace, y};
+    rc = validate(q, kernel_h, kernel_w, ptrs, 3);
+    if (rc)
+        return rc;
+    // the merged layer predicts one set of offsets per INPUT pixel: the window must keep the map's size
+    if (q.Ho != H || q.Wo != W || kernel_h != 3)
+        return DCNV4_ERR_UNSUPPORTED;
+    const long long need = dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, light ? 1 : 0);
+    if (workspace_bytes < need)
+        return DCNV4_ERR_SHAPE;
+    const long long P = (long long)N * H * W, es = esize(dtype);
+    const int C = G * Cg;
+    char *om = (char *)workspace;
+    char *value = om + align256((size_t)(P * G * 32 * es));
+    char *y_op = value + align256((size_t)(P * C * es));
+    // both layers that read x in one pass, then the operator on the merged buffer, then the output layer
+    LinGeo first, last;
+    rc = begin_linear(&first, x, P, C, dtype);
+    if (!rc && !light)
+        rc = add_linear_segment(&first, P, C, dtype, w_in, b_in, value, C);
+    if (!rc)
+        rc = add_linear_segment(&first, P, C, dtype, w_om, b_om, om, G * 32);
+    if (!rc && !light) {
+        rc = begin_linear(&last, y_op, P, C, dtype);
+        if (!rc)
+            rc = add_linear_segment(&last, P, C, dtype, w_out, b_out, y, C);
+    }
+    if (rc)
+        return rc;
+    hipStream_t s = (hipStream_t)stream;
+    rc = launch_linear(x, first, dtype, s);
+    if (rc)
+        return rc;
+    rc = forward_impl(light ? x : (const void *)value, om, nullptr, light ? y : (void *)y_op, N, H, W, G, Cg, kernel_h,
+                      kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype, stream, true);
+    if (rc || light)
+        return rc;
+    return launch_linear(y_op, last, dtype, s);
 }
 
 int dcnv4_set_option(const char *key, int value)

@@ -98,3 +98,33 @@ def merge_offset_mask(offset, mask, pad_value=0.0):
     om[..., :2 * K] = offset.reshape(N, Ho, Wo, G, 2 * K)
     om[..., 2 * K:3 * K] = mask
     return om
+
+
+def make_module_params(cfg: Config, dtype: str = "f32", seed: int = 0, lightweight: bool = False, pad_value: float = 0.0):
+    """Seeded random weights of the module's linear layers (numpy, `dtype`), sized so that with x ~ N(0,1)
+    the predicted offsets have a standard deviation of about cfg.sigma pixels and the modulation scalars
+    and projected values of about 1 -- the distributions of the operator-level inputs above:
+      w_om [G*27, C] / b_om [G*27]: per group 18 offset rows, then 9 scalar rows (what the single layer
+      of the module has); w_om_padded [G*32, C] / b_om_padded [G*32]: the same rows in the 32-entry
+      layout, the five padding rows filled with pad_value (their outputs must be ignored);
+      w_in, b_in, w_out, b_out [C, C] / [C] unless lightweight."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed + 7919)
+    C, G = cfg.C, cfg.G
+    K = cfg.kernel * cfg.kernel
+    scale = torch.cat([torch.full((2 * K,), cfg.sigma), torch.ones(K)]).repeat(G)[:, None] / float(np.sqrt(C))
+    w_om = torch.randn((G * 3 * K, C), generator=gen) * scale
+    b_om = 0.1 * torch.randn((G * 3 * K,), generator=gen)
+    out = {"w_om": w_om, "b_om": b_om}
+    if not lightweight:
+        for name in ("in", "out"):
+            out["w_" + name] = torch.randn((C, C), generator=gen) / float(np.sqrt(C))
+            out["b_" + name] = 0.1 * torch.randn((C,), generator=gen)
+    np_dtype = {"f32": np.float32, "f16": np.float16}[dtype]
+    out = {k: v.numpy().astype(np_dtype) for k, v in out.items()}
+    wp = np.full((G, 32, C), pad_value, dtype=np_dtype)
+    bp = np.full((G, 32), pad_value, dtype=np_dtype)
+    wp[:, :3 * K] = out["w_om"].reshape(G, 3 * K, C)
+    bp[:, :3 * K] = out["b_om"].reshape(G, 3 * K)
+    out["w_om_padded"], out["b_om_padded"] = wp.reshape(G * 32, C), bp.reshape(G * 32)
+    return out

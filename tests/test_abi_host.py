@@ -93,6 +93,30 @@ def test_merged_entry_points_validate_on_the_host_too():
     assert dcn.dcnv4_backward_merged_algorithmic_bytes(*c2, dcn.DCNV4_F32) == 4 * 64 * 56 * 56 * (3 * 128 + 64 * 8)
 
 
+def test_linear_and_module_entry_points_validate_on_the_host():
+    lib = dcn.load_library()
+    lin = lambda x=A, w=A, b=None, y=A, P=100, K=64, Nout=32, dtype=0: lib.dcnv4_linear(x, w, b, y, P, K, Nout, dtype, None)
+    assert lin(x=None) == 1 and lin(w=None) == 1 and lin(y=None) == 1
+    assert lin(P=0) == 2 and lin(K=0) == 2 and lin(Nout=0) == 2
+    assert lin(K=12) == 3 and lin(K=8, dtype=1) == 3 and lin(Nout=40) == 3 and lin(dtype=2) == 3
+    assert lin(P=1 << 24, K=64) == 3                                 # x of 4 GiB: beyond 32-bit byte offsets
+    assert lin(x=A + 8) == 4 and lin(w=A + 4) == 4 and lin(y=A + 2) == 4 and lin(b=A + 2) == 4
+
+    def mod(x=A, w_in=A, w_om=A, w_out=A, ws=A, ws_bytes=1 << 40, y=A, N=1, H=14, W=14, G=4, Cg=16, k=3, s=1, p=1, d=1, dtype=0):
+        return lib.dcnv4_module_forward(x, w_in, None, w_om, None, w_out, None, ws, ws_bytes, y, N, H, W, G, Cg, k, k, s, s, p, p,
+                                        d, d, 1.0, dtype, None)
+    assert mod(x=None) == 1 and mod(w_om=None) == 1 and mod(ws=None) == 1 and mod(y=None) == 1
+    assert mod(w_in=None) == 1 and mod(w_out=None) == 1              # the projections come together
+    assert mod(N=0) == 2 and mod(ws_bytes=1000) == 2
+    assert mod(p=0) == 3 and mod(s=2) == 3 and mod(k=5, p=2) == 3 and mod(k=1, p=0) == 3 and mod(Cg=12) == 3
+    assert mod(G=3, Cg=16) == 3                                      # C = 48: not a multiple of 32 output channels
+    assert mod(ws=A + 8) == 4
+    P, C, G = 64 * 56 * 56, 128, 8
+    assert dcn.dcnv4_module_workspace_bytes(64, 56, 56, G, 16, dcn.DCNV4_F16, True) == 2 * P * G * 32
+    assert dcn.dcnv4_module_workspace_bytes(64, 56, 56, G, 16, dcn.DCNV4_F16, False) == 2 * P * (G * 32 + 2 * C)
+    assert dcn.dcnv4_module_workspace_bytes(0, 56, 56, G, 16, dcn.DCNV4_F16, False) == -1
+
+
 def test_options():
     assert dcn.dcnv4_last_kernel_name(0) is None or dcn.dcnv4_last_kernel_name(0).startswith("dcnv4_fwd")
     for key, bad in (("fwd_cpt", 5), ("nonsense", 1), ("fwd_path", 4), ("bwd_path", 3), ("fwd_single", 3), ("wg_per_cu", 17), ("halo", 65), ("lds_kb", 4), ("fwd_threads", 100)):
