@@ -28,7 +28,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets rotated per leg")
-    ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16,fwd_f16_merged,bwd_f32_merged,fwd_f16_softmax,bwd_f32_softmax",
+    ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16,fwd_f16_merged,bwd_f32_merged,fwd_f16_softmax,bwd_f32_softmax,"
+                                      "module_f16,modulelite_f16,module_f32,modulelite_f32",
                     help="fwd|bwd _ f16|f32 [_merged: offsets and mask values in one [N,Ho,Wo,G,32] buffer | "
                          "_softmax: the mask tensor holds logits, normalised over the 9 taps (DCNv3 form)]")
     ap.add_argument("--workload", default="c2")
@@ -194,6 +195,50 @@ def run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_outpu
     return rec, y
 
 
+def run_module_leg(torch, dcn, lib, stream, cfg, leg, a, steps):
+    """Times the module forward ("module_f16": both projections; "modulelite_f16": without them) on workload
+    cfg.  Bytes: every tensor between the layers counted once per write and once per read."""
+    from paper_2401_06197_amd.synth import make_inputs, make_module_params
+    dev = torch.device("cuda:0")
+    kind, dt = leg.split("_")[:2]
+    light = kind == "modulelite"
+    tdt = {"f16": torch.float16, "f32": torch.float32}[dt]
+    es = 2 if dt == "f16" else 4
+    x0 = torch.from_numpy(make_inputs(cfg, dt, seed=0)["x"]).to(dev)
+    prm = {k: torch.from_numpy(v).to(dev) for k, v in make_module_params(cfg, dt, seed=0, lightweight=light).items()}
+    P = cfg.N * cfg.H * cfg.W
+    moved = P * es * ((2 * cfg.C + 2 * 32 * cfg.G) if light else (6 * cfg.C + 2 * 32 * cfg.G))
+    one_set = 2 * x0.numel() * es + dcn.dcnv4_module_workspace_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, {"f16": 1, "f32": 0}[dt], light)
+    nsets = max(a.sets, min(16, -(-(320 << 20) // one_set)))
+    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    ys = [torch.empty_like(x0) for _ in range(nsets)]
+    wss = [torch.empty(one_set - 2 * x0.numel() * es, dtype=torch.uint8, device=dev) for _ in range(nsets)]
+    geo = dict(kernel=cfg.kernel, stride=cfg.stride, pad=cfg.pad, dilation=cfg.dilation, offset_scale=cfg.offset_scale)
+    argv = [dcn.dcnv4_module_forward(x, prm["w_om_padded"], prm["b_om_padded"], cfg.G, w_in=prm.get("w_in"), b_in=prm.get("b_in"),
+                                     w_out=prm.get("w_out"), b_out=prm.get("b_out"), workspace=w, out=y, stream=stream,
+                                     prepare_only=True, **geo) for x, y, w in zip(xs, ys, wss)]
+
+    def launch(i):
+        rc = lib.dcnv4_module_forward(*argv[i])
+        if rc:
+            raise dcn.Dcnv4Error(rc, leg)
+    torch.cuda.synchronize()
+    t = time_leg(torch, stream, launch, nsets, steps, a.warmup, a.cold_only)
+    rec = {"workload": cfg.name, "kernel": "dcnv4_linear_kernel + " + str(dcn.dcnv4_last_kernel_name(0)), "steps": steps,
+           "us_per_launch": round(t["cold"] * 1e3, 3), "out_elems_per_s": P * cfg.C / (t["cold"] * 1e-3),
+           "moved_bytes": moved, "GBps": moved / (t["cold"] * 1e-3) / 1e9,
+           "frac_of_hbm_peak": moved / (t["cold"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "hot_us_per_launch": None if a.cold_only else round(t["hot"] * 1e3, 3), "buffer_sets": nsets}
+    del xs, ys, wss, prm
+    torch.cuda.empty_cache()
+    return rec
+
+
+# the paper's module-level numbers (appendix, A100, microseconds, fp32 / fp16; full module, lightweight): context
+PAPER_A100_MODULE_US = {"paper_56x56x128": ((1280, 873), (762, 547)), "paper_28x28x256": ((738, 483), (419, 313)),
+                        "paper_14x14x512": ((452, 324), (375, 192)), "paper_7x7x1024": ((334, 265), (306, 130)),
+                        "paper_14x14x768": ((787, 463), (389, 249))}
+
 # the paper's op-level numbers (Tab. 2 and 3, A100 80GB SXM, microseconds, fp32 / fp16): context, not a target
 PAPER_A100_US = {"paper_56x56x128": (606, 404), "paper_28x28x256": (303, 230), "paper_14x14x512": (145, 123),
                  "paper_7x7x1024": (73.0, 68.0), "paper_14x14x768": (224, 147), "paper_200x320x128": (210, 136),
@@ -237,6 +282,9 @@ def main():
     head_y = None
     for leg in legs_wanted:
         steps = a.steps if leg.startswith("fwd") else max(1, a.steps // 4)
+        if leg.startswith("module"):
+            legs[leg] = run_module_leg(torch, dcn, lib, stream, cfg, leg, a, steps)
+            continue
         legs[leg], y = run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_output=leg == legs_wanted[0])
         if leg == legs_wanted[0]:
             head_y = y
@@ -252,6 +300,11 @@ def main():
         for name, (us32, us16) in PAPER_A100_US.items():
             for leg, ref_us in (("fwd_f32", us32), ("fwd_f16", us16)):
                 r, _ = run_leg(torch, dcn, lib, stream, CONFIGS[name], leg, a, {}, a.steps)
+                r["paper_a100_us"] = ref_us
+                legs[f"{leg}@{name}"] = r
+        for name, (full, lite) in PAPER_A100_MODULE_US.items():
+            for leg, ref_us in (("module_f32", full[0]), ("module_f16", full[1]), ("modulelite_f32", lite[0]), ("modulelite_f16", lite[1])):
+                r = run_module_leg(torch, dcn, lib, stream, CONFIGS[name], leg, a, max(1, a.steps // 4))
                 r["paper_a100_us"] = ref_us
                 legs[f"{leg}@{name}"] = r
 

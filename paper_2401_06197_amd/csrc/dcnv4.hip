@@ -1513,11 +1513,21 @@ int begin_linear(LinGeo *g, const void *x, long long P, int K, int dtype)
 
 int launch_linear(const void *x, const LinGeo &g, int dtype, hipStream_t s)
 {
-    const unsigned grid = (unsigned)((g.P + kLinPixels - 1) / kLinPixels);
+    const int tiles = (g.P + kLinPixels - 1) / kLinPixels;
+    // maps of few pixels and many channels: the passes over blocks of output channels are spread over
+    // workgroups as well, until there are about two workgroups per compute unit
+    int npass = 0;
+    for (int i = 0; i < g.nseg; ++i)
+        npass += g.seg[i].nblocks;
+    const int want = 2 * device_cus();
+    int split = (want + tiles - 1) / tiles;
+    if (split > npass) split = npass;
+    if (split < 1) split = 1;
+    const dim3 grid((unsigned)tiles, (unsigned)split);
     if (dtype == DCNV4_F16)
-        hipLaunchKernelGGL(dcnv4_linear_kernel<_Float16>, dim3(grid), dim3(256), 0, s, (const _Float16 *)x, g);
+        hipLaunchKernelGGL(dcnv4_linear_kernel<_Float16>, grid, dim3(256), 0, s, (const _Float16 *)x, g);
     else
-        hipLaunchKernelGGL(dcnv4_linear_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)x, g);
+        hipLaunchKernelGGL(dcnv4_linear_kernel<float>, grid, dim3(256), 0, s, (const float *)x, g);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
 }
 
