@@ -277,6 +277,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     legs_wanted = [s for s in a.legs.split(",") if s]
+    if not legs_wanted or legs_wanted[0].startswith("module"):
+        print("bench.py: the first leg is the headline and must be an operator leg (fwd_* or bwd_*)", file=sys.stderr)
+        sys.exit(2)
     legs = {}
     host_inputs = {}
     head_y = None
