@@ -1524,10 +1524,18 @@ int launch_linear(const void *x, const LinGeo &g, int dtype, hipStream_t s)
     if (split > npass) split = npass;
     if (split < 1) split = 1;
     const dim3 grid((unsigned)tiles, (unsigned)split);
-    if (dtype == DCNV4_F16)
-        hipLaunchKernelGGL(dcnv4_linear_kernel<_Float16>, grid, dim3(256), 0, s, (const _Float16 *)x, g);
-    else
-        hipLaunchKernelGGL(dcnv4_linear_kernel<float>, grid, dim3(256), 0, s, (const float *)x, g);
+    const bool single = g.nchunks == 1;
+    if (dtype == DCNV4_F16) {
+        if (single)
+            hipLaunchKernelGGL((dcnv4_linear_kernel<_Float16, true>), grid, dim3(256), 0, s, (const _Float16 *)x, g);
+        else
+            hipLaunchKernelGGL((dcnv4_linear_kernel<_Float16, false>), grid, dim3(256), 0, s, (const _Float16 *)x, g);
+    } else {
+        if (single)
+            hipLaunchKernelGGL((dcnv4_linear_kernel<float, true>), grid, dim3(256), 0, s, (const float *)x, g);
+        else
+            hipLaunchKernelGGL((dcnv4_linear_kernel<float, false>), grid, dim3(256), 0, s, (const float *)x, g);
+    }
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
 }
 
