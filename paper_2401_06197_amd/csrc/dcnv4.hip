@@ -884,7 +884,8 @@ int make_tgeo(const Problem &q, int threads, int mode, TGeo *out, int cg_kernel 
     p.softmax = q.softmax;
     p.og_bytes = (int)((q.merged ? 32 : 18) * es);
     p.mg_bytes = (int)((q.merged ? 32 : 9) * es);
-    if (pgi * p.og_bytes >= (1LL << 31))
+    // (idle lanes point at (pixel, group) number 2^24 of the image, which has to lie past its end)
+    if (pgi * p.og_bytes >= (1LL << 31) || pgi >= (1LL << 24))
         return DCNV4_ERR_UNSUPPORTED;
     p.off_img_bytes = (int)(pgi * p.og_bytes);
     p.msk_img_bytes = (int)(pgi * p.mg_bytes);
