@@ -169,12 +169,15 @@ def _stored(a, storage):
     return a if storage is None else a.astype(storage).astype(np.float64)
 
 
-def module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_out=None, storage=None, **kw):
+def module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_out=None, w_dw=None, b_dw=None,
+                   storage=None, **kw):
     """The DCNv4 module (Sec. 3.1 last paragraph of the DCNv3 review, Sec. 3.2 "Micro design", and the
     two variants of the module-level benchmark in the appendix), no depthwise convolution:
         value = x W_in^T + b_in                      (left out in the lightweight variant: value = x)
-        om    = x W_om^T + b_om                      ONE linear layer: per group 2K offsets (tap-major,
-                                                     width then height), then the K modulation scalars
+        om    = x' W_om^T + b_om                     ONE linear layer: per group 2K offsets (tap-major,
+                                                     width then height), then the K modulation scalars;
+                                                     x' = depthwise3x3(x) if w_dw is given (the separable
+                                                     structure of Sec. 3.2), else x
         y_op  = Eq. 1-2 on (value, offsets, scalars) no softmax
         y     = y_op W_out^T + b_out                 (left out in the lightweight variant)
     x [N,H,W,C]; w_om [G*3K, C]; w_in, w_out [C, C] (both given, or both None).  The window must keep
@@ -190,7 +193,8 @@ def module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_out=Non
     if _f64(w_om).shape != (G * 3 * K, C):
         raise ValueError(f"w_om of shape {np.shape(w_om)}, expected {(G * 3 * K, C)}")
     value = x if w_in is None else _stored(linear(x, w_in, b_in), storage)
-    om = _stored(linear(x, w_om, b_om), storage).reshape(N, H, W, G, 3 * K)
+    x_om = x if w_dw is None else _stored(depthwise3x3(x, w_dw, b_dw), storage)
+    om = _stored(linear(x_om, w_om, b_om), storage).reshape(N, H, W, G, 3 * K)
     offset, mask = split_merged(om, kw.get("kernel", 3))
     y = forward(value, offset, mask, **kw)
     if y.shape[1:3] != (H, W):
@@ -198,3 +202,23 @@ def module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_out=Non
     if w_out is None:
         return y
     return linear(_stored(y, storage), w_out, b_out)
+
+
+def depthwise3x3(x, w, b=None):
+    """The 3x3 depthwise convolution of the separable structure the module uses to compute offsets and
+    scalars (Sec. 3.2 "Micro design"), zero padding, stride 1:
+        y[n,h,w,c] = b[c] + sum_{i,j in 0..2} w[i,j,c] * x[n, h+i-1, w+j-1, c]     (x = 0 outside the map)
+    x [N,H,W,C]; w [3,3,C] (i: height tap, j: width tap); b [C] or None."""
+    x, w = _f64(x), _f64(w)
+    N, H, W, C = x.shape
+    if w.shape != (3, 3, C):
+        raise ValueError(f"depthwise weights of shape {w.shape}, expected {(3, 3, C)}")
+    xp = np.zeros((N, H + 2, W + 2, C))
+    xp[:, 1:-1, 1:-1] = x
+    y = np.zeros_like(x)
+    for i in range(3):
+        for j in range(3):
+            y += w[i, j] * xp[:, i:i + H, j:j + W]
+    if b is not None:
+        y = y + _f64(b)
+    return y

@@ -452,3 +452,47 @@ def test_module_storage_rounding_and_argument_checks():
         oracle.module_forward(x, w_om, b_om, G, pad=0)               # a window that shrinks the map
     np.testing.assert_array_equal(oracle.linear(np.array([[1.0, 2.0]]), np.array([[3.0, 4.0], [5.0, 6.0], [7.0, 8.0]]),
                                                 np.array([0.5, 0.0, -1.0])), [[11.5, 17.0, 22.0]])
+
+
+def test_depthwise_convolution_against_the_library_routine_and_closed_forms():
+    rng = np.random.default_rng(31)
+    N, H, W, C = 2, 6, 7, 5
+    x, w, b = rng.standard_normal((N, H, W, C)), rng.standard_normal((3, 3, C)), rng.standard_normal(C)
+    y = oracle.depthwise3x3(x, w, b)
+    # library route: grouped conv2d in fp64 (weight [C,1,kh,kw], cross-correlation like ours)
+    yt = F.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2), torch.from_numpy(w).permute(2, 0, 1)[:, None], torch.from_numpy(b),
+                  padding=1, groups=C).permute(0, 2, 3, 1).numpy()
+    np.testing.assert_allclose(y, yt, rtol=1e-12, atol=1e-12)
+    centre = np.zeros((3, 3, C))
+    centre[1, 1] = 1.0
+    np.testing.assert_array_equal(oracle.depthwise3x3(x, centre), x)
+    np.testing.assert_allclose(oracle.depthwise3x3(x, np.ones((3, 3, C))), box3(x), rtol=1e-12, atol=1e-12)
+    down = np.zeros((3, 3, C))
+    down[2, 1] = 1.0                                               # tap (i=2, j=1): the pixel one row below
+    want = np.zeros_like(x)
+    want[:, :-1] = x[:, 1:]
+    np.testing.assert_array_equal(oracle.depthwise3x3(x, down), want)
+
+
+def test_module_with_the_depthwise_convolution_in_front_of_the_offset_layer():
+    """The depthwise output only feeds the offset/scalar layer: with a centre-tap depthwise kernel the module
+    equals the one without it, and steering by a SHIFTED copy of the input (tap one column to the right)
+    moves the closed form of the steering test by one pixel."""
+    rng = np.random.default_rng(32)
+    G, Cg, H, W = 2, 4, 9, 10
+    C = G * Cg
+    x = rng.standard_normal((1, H, W, C))
+    w_om, b_om = 0.2 * rng.standard_normal((G * 27, C)), rng.standard_normal(G * 27)
+    centre = np.zeros((3, 3, C))
+    centre[1, 1] = 1.0
+    plain = oracle.module_forward(x, w_om, b_om, G)
+    np.testing.assert_array_equal(oracle.module_forward(x, w_om, b_om, G, w_dw=centre), plain)
+    right = np.zeros((3, 3, C))
+    right[1, 2] = 1.0
+    shifted = np.zeros_like(x)
+    shifted[:, :, :-1] = x[:, :, 1:]
+    om_from_shifted = oracle.linear(shifted, w_om, b_om).reshape(1, H, W, G, 27)
+    off, m = oracle.split_merged(om_from_shifted)
+    np.testing.assert_allclose(oracle.module_forward(x, w_om, b_om, G, w_dw=right), oracle.forward(x, off, m), rtol=1e-12,
+                               atol=1e-12)
+    assert not np.allclose(oracle.module_forward(x, w_om, b_om, G, w_dw=right), plain)
