@@ -29,7 +29,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets rotated per leg")
     ap.add_argument("--legs", default="fwd_f16,fwd_f32,bwd_f32,bwd_f16,fwd_f16_merged,bwd_f32_merged,fwd_f16_softmax,bwd_f32_softmax,"
-                                      "module_f16,modulelite_f16,module_f32,modulelite_f32",
+                                      "module_f16,modulelite_f16,module_f32,modulelite_f32,module_f16_dw",
                     help="fwd|bwd _ f16|f32 [_merged: offsets and mask values in one [N,Ho,Wo,G,32] buffer | "
                          "_softmax: the mask tensor holds logits, normalised over the 9 taps (DCNv3 form)]")
     ap.add_argument("--workload", default="c2")
@@ -196,26 +196,28 @@ def run_leg(torch, dcn, lib, stream, cfg, leg, a, host_inputs, steps, keep_outpu
 
 
 def run_module_leg(torch, dcn, lib, stream, cfg, leg, a, steps):
-    """Times the module forward ("module_f16": both projections; "modulelite_f16": without them) on workload
+    """Times the module forward ("module_f16": both projections; "modulelite_f16": without them; suffix "_dw":
+    with the depthwise convolution in front of the offset/scalar layer) on workload
     cfg.  Bytes: every tensor between the layers counted once per write and once per read."""
     from paper_2401_06197_amd.synth import make_inputs, make_module_params
     dev = torch.device("cuda:0")
     kind, dt = leg.split("_")[:2]
     light = kind == "modulelite"
+    dw = leg.endswith("_dw")
     tdt = {"f16": torch.float16, "f32": torch.float32}[dt]
     es = 2 if dt == "f16" else 4
     x0 = torch.from_numpy(make_inputs(cfg, dt, seed=0)["x"]).to(dev)
-    prm = {k: torch.from_numpy(v).to(dev) for k, v in make_module_params(cfg, dt, seed=0, lightweight=light).items()}
+    prm = {k: torch.from_numpy(v).to(dev) for k, v in make_module_params(cfg, dt, seed=0, lightweight=light, depthwise=dw).items()}
     P = cfg.N * cfg.H * cfg.W
-    moved = P * es * ((2 * cfg.C + 2 * 32 * cfg.G) if light else (6 * cfg.C + 2 * 32 * cfg.G))
-    one_set = 2 * x0.numel() * es + dcn.dcnv4_module_workspace_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, {"f16": 1, "f32": 0}[dt], light)
+    moved = P * es * ((2 * cfg.C + 2 * 32 * cfg.G) if light else (6 * cfg.C + 2 * 32 * cfg.G)) + (P * es * 3 * cfg.C if dw else 0)
+    one_set = 2 * x0.numel() * es + dcn.dcnv4_module_workspace_bytes(cfg.N, cfg.H, cfg.W, cfg.G, cfg.Cg, {"f16": 1, "f32": 0}[dt], light, dw)
     nsets = max(a.sets, min(16, -(-(320 << 20) // one_set)))
     xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
     ys = [torch.empty_like(x0) for _ in range(nsets)]
     wss = [torch.empty(one_set - 2 * x0.numel() * es, dtype=torch.uint8, device=dev) for _ in range(nsets)]
     geo = dict(kernel=cfg.kernel, stride=cfg.stride, pad=cfg.pad, dilation=cfg.dilation, offset_scale=cfg.offset_scale)
     argv = [dcn.dcnv4_module_forward(x, prm["w_om_padded"], prm["b_om_padded"], cfg.G, w_in=prm.get("w_in"), b_in=prm.get("b_in"),
-                                     w_out=prm.get("w_out"), b_out=prm.get("b_out"), workspace=w, out=y, stream=stream,
+                                     w_out=prm.get("w_out"), b_out=prm.get("b_out"), w_dw=prm.get("w_dw"), b_dw=prm.get("b_dw"), workspace=w, out=y, stream=stream,
                                      prepare_only=True, **geo) for x, y, w in zip(xs, ys, wss)]
 
     def launch(i):

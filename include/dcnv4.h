@@ -149,21 +149,34 @@ int dcnv4_backward_softmax(const void *x, const void *offset, const void *mask_l
 int dcnv4_linear(const void *x, const void *w, const void *b, void *y,
                  long long P, int K, int Nout, int dtype, void *stream);
 
+/* The 3x3 depthwise convolution of the separable structure that computes offsets and scalars in the
+ * module (Sec. 3.2 "Micro design"), zero padding, stride 1, channel-last:
+ *     y[n,h,w,c] = b[c] + sum_{i,j in 0..2} w[i][j][c] * x[n, h+i-1, w+j-1, c]      (x = 0 outside the map)
+ * Device pointers, 16-byte aligned: x, y [N,H,W,C]; w [3][3][C] (i: height tap, j: width tap); b [C] or
+ * NULL.  fp32 accumulation, one rounding at the store.  Needs C * element size a multiple of 16 bytes and
+ * the tensor below 2 GiB (else DCNV4_ERR_UNSUPPORTED). */
+int dcnv4_depthwise3x3(const void *x, const void *w, const void *b, void *y,
+                       int N, int H, int W, int C, int dtype, void *stream);
+
 /* Forward of the DCNv4 module (Sec. 3.2 "Micro design"; the two variants of the module-level
- * benchmark of the appendix), without the optional depthwise convolution:
+ * benchmark of the appendix):
  *     value = x W_in^T + b_in          (w_in == w_out == NULL: the "lightweight" variant, value = x)
- *     om    = x W_om^T + b_om          ONE layer for offsets and scalars, in the merged layout above:
+ *     x'    = depthwise3x3(x; w_dw, b_dw)   (w_dw == NULL: x' = x -- the paper notes the convolution can go
+ *                                      where latency matters)
+ *     om    = x' W_om^T + b_om         ONE layer for offsets and scalars, in the merged layout above:
  *                                      w_om [G*32][C], b_om [G*32]; row g*32 + e produces entry e of
  *                                      group g (0..17 offsets, 18..26 scalars, 27..31 ignored)
  *     y_op  = dcnv4_forward_merged(value, om)
  *     y     = y_op W_out^T + b_out     (left out in the lightweight variant: y = y_op)
- * x, y [N,H,W,C], C = G*Cg; w_in, w_out [C][C]; biases may be NULL.  The window must be 3x3 and keep
- * the map's size (stride 1, pad = dilation), C * element size a multiple of 32 bytes.  `workspace`:
- * device memory of at least dcnv4_module_workspace_bytes() bytes, 16-byte aligned, owned by the caller;
- * it holds om, value and y_op during the call and may be reused afterwards.  The value projection
- * and the merged layer run as one kernel that reads x once.  Tensors between the layers are stored in
- * `dtype`.  On an error y is untouched (the workspace may have been written). */
+ * x, y [N,H,W,C], C = G*Cg; w_in, w_out [C][C]; w_dw [3][3][C]; biases may be NULL.  The window must be
+ * 3x3 and keep the map's size (stride 1, pad = dilation), C * element size a multiple of 32 bytes.
+ * `workspace`: device memory of at least dcnv4_module_workspace_bytes() bytes, 16-byte aligned, owned by
+ * the caller; it holds om, value, y_op and x' during the call and may be reused afterwards.  Without the
+ * depthwise convolution the value projection and the merged layer run as one kernel that reads x once.
+ * Tensors between the layers are stored in `dtype`.  On an error y is untouched (the workspace may
+ * have been written). */
 int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in,
+                         const void *w_dw, const void *b_dw,
                          const void *w_om, const void *b_om,
                          const void *w_out, const void *b_out,
                          void *workspace, long long workspace_bytes, void *y,
@@ -172,9 +185,10 @@ int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in,
                          int pad_h, int pad_w, int dil_h, int dil_w,
                          float offset_scale, int dtype, void *stream);
 
-/* Bytes of workspace dcnv4_module_forward needs (lightweight != 0: without the two projections);
- * -1 for a bad argument.  Host-only helper. */
-long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int dtype, int lightweight);
+/* Bytes of workspace dcnv4_module_forward needs (lightweight != 0: without the two projections;
+ * depthwise != 0: with the depthwise convolution); -1 for a bad argument.  Host-only helper. */
+long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int dtype, int lightweight,
+                                       int depthwise);
 
 /* Bytes the ideal memory-access model of Sec. 3.2 ("2HWC + 27HWG", every value touched
  * once) assigns to one forward call: x + offset + mask + y.  Host-only helper. */

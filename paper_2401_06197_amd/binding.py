@@ -17,7 +17,7 @@ DCNV4_OK = 0
 EXPORTS = (
     "dcnv4_output_hw", "dcnv4_forward", "dcnv4_backward", "dcnv4_forward_merged", "dcnv4_backward_merged",
     "dcnv4_forward_softmax", "dcnv4_backward_softmax",
-    "dcnv4_linear", "dcnv4_module_forward", "dcnv4_module_workspace_bytes",
+    "dcnv4_linear", "dcnv4_depthwise3x3", "dcnv4_module_forward", "dcnv4_module_workspace_bytes",
     "dcnv4_forward_algorithmic_bytes", "dcnv4_backward_algorithmic_bytes",
     "dcnv4_forward_merged_algorithmic_bytes", "dcnv4_backward_merged_algorithmic_bytes",
     "dcnv4_set_option", "dcnv4_last_kernel_name", "dcnv4_status_string",
@@ -65,9 +65,11 @@ def load_library():
         f.restype = ctypes.c_longlong
     lib.dcnv4_linear.argtypes = [vp] * 4 + [ctypes.c_longlong, ci, ci, ci, vp]
     lib.dcnv4_linear.restype = ci
-    lib.dcnv4_module_forward.argtypes = [vp] * 8 + [ctypes.c_longlong, vp] + geo
+    lib.dcnv4_depthwise3x3.argtypes = [vp] * 4 + [ci] * 5 + [vp]
+    lib.dcnv4_depthwise3x3.restype = ci
+    lib.dcnv4_module_forward.argtypes = [vp] * 10 + [ctypes.c_longlong, vp] + geo
     lib.dcnv4_module_forward.restype = ci
-    lib.dcnv4_module_workspace_bytes.argtypes = [ci] * 7
+    lib.dcnv4_module_workspace_bytes.argtypes = [ci] * 8
     lib.dcnv4_module_workspace_bytes.restype = ctypes.c_longlong
     lib.dcnv4_set_option.argtypes = [ctypes.c_char_p, ci]
     lib.dcnv4_set_option.restype = ci
@@ -322,16 +324,40 @@ def dcnv4_linear(x, w, b=None, out=None, stream=None, prepare_only=False):
     return out
 
 
-def dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, lightweight):
-    return int(load_library().dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, int(bool(lightweight))))
+def dcnv4_depthwise3x3(x, w, b=None, out=None, stream=None):
+    """y[n,h,w,c] = b[c] + sum_ij w[i,j,c] * x[n,h+i-1,w+j-1,c] (zero padding): x [N,H,W,C], w [3,3,C]."""
+    import torch
+    if x.dim() != 4 or tuple(w.shape) != (3, 3, x.shape[3]) or (b is not None and tuple(b.shape) != (x.shape[3],)):
+        raise ValueError("dcnv4: expected x [N,H,W,C], w [3,3,C], b [C]")
+    for name, t in (("x", x), ("w", w)) + ((("b", b),) if b is not None else ()):
+        _check(name, t, x)
+    if out is None:
+        out = torch.empty_like(x)
+    else:
+        _check("out", out, x)
+        if out.shape != x.shape:
+            raise ValueError("dcnv4: out has the wrong shape")
+    N, H, W, C = x.shape
+    with torch.cuda.device(x.device):
+        rc = load_library().dcnv4_depthwise3x3(x.data_ptr(), w.data_ptr(), b.data_ptr() if b is not None else None,
+                                               out.data_ptr(), N, H, W, C, _dtype_code(x), _stream_ptr(stream, x.device))
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_depthwise3x3")
+    return out
 
 
-def dcnv4_module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_out=None, kernel=3, stride=1, pad=1,
-                         dilation=1, offset_scale=1.0, workspace=None, out=None, stream=None, prepare_only=False):
+def dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, lightweight, depthwise=False):
+    return int(load_library().dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, int(bool(lightweight)), int(bool(depthwise))))
+
+
+def dcnv4_module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_out=None, w_dw=None, b_dw=None, kernel=3,
+                         stride=1, pad=1, dilation=1, offset_scale=1.0, workspace=None, out=None, stream=None,
+                         prepare_only=False):
     """Forward of the DCNv4 module: (value projection,) ONE linear layer for offsets and modulation
     scalars, the operator, (output projection).  w_om [G*32, C] / b_om [G*32] in the merged layout
     (row g*32 + e: entry e of group g; 0..17 offsets, 18..26 scalars, 27..31 ignored); w_in, w_out
-    [C, C] or both None (the lightweight variant)."""
+    [C, C] or both None (the lightweight variant); w_dw [3, 3, C] / b_dw [C]: the optional depthwise
+    convolution in front of the offset/scalar layer."""
     import torch
     if x.dim() != 4 or x.shape[3] % G:
         raise ValueError("dcnv4: expected x [N,H,W,C] with C a multiple of G")
@@ -340,7 +366,7 @@ def dcnv4_module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_o
     if (w_in is None) != (w_out is None):
         raise ValueError("dcnv4: the input and output projections come together")
     shapes = [("w_om", w_om, (G * 32, C)), ("b_om", b_om, (G * 32,)), ("w_in", w_in, (C, C)), ("b_in", b_in, (C,)),
-              ("w_out", w_out, (C, C)), ("b_out", b_out, (C,))]
+              ("w_out", w_out, (C, C)), ("b_out", b_out, (C,)), ("w_dw", w_dw, (3, 3, C)), ("b_dw", b_dw, (C,))]
     for name, t, shape in shapes:
         if t is not None:
             _check(name, t, x)
@@ -348,7 +374,7 @@ def dcnv4_module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_o
                 raise ValueError(f"dcnv4: {name} must have shape {shape}")
     _check("x", x, x)
     light = w_in is None
-    need = dcnv4_module_workspace_bytes(N, H, W, G, C // G, _dtype_code(x), light)
+    need = dcnv4_module_workspace_bytes(N, H, W, G, C // G, _dtype_code(x), light, w_dw is not None)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
     elif not workspace.is_cuda or workspace.device != x.device or not workspace.is_contiguous():
@@ -360,7 +386,7 @@ def dcnv4_module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_o
         if out.shape != x.shape:
             raise ValueError("dcnv4: out has the wrong shape")
     ptr = lambda t: t.data_ptr() if t is not None else None
-    args = (x.data_ptr(), ptr(w_in), ptr(b_in), w_om.data_ptr(), ptr(b_om), ptr(w_out), ptr(b_out), workspace.data_ptr(),
+    args = (x.data_ptr(), ptr(w_in), ptr(b_in), ptr(w_dw), ptr(b_dw), w_om.data_ptr(), ptr(b_om), ptr(w_out), ptr(b_out), workspace.data_ptr(),
             workspace.numel() * workspace.element_size(), out.data_ptr(), N, H, W, G, C // G, kh, kw, sh, sw, ph, pw,
             dh, dw, float(offset_scale), _dtype_code(x), _stream_ptr(stream, x.device))
     if prepare_only:

@@ -1540,6 +1540,41 @@ int launch_linear(const void *x, const LinGeo &g, int dtype, hipStream_t s)
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
 }
 
+int launch_depthwise(const void *x, const void *w, const void *b, void *y, int N, int H, int W, int C, int dtype,
+                     hipStream_t s)
+{
+    if (!x || !w || !y)
+        return DCNV4_ERR_NULL;
+    if (N < 1 || H < 1 || W < 1 || C < 1)
+        return DCNV4_ERR_SHAPE;
+    if (dtype != DCNV4_F32 && dtype != DCNV4_F16)
+        return DCNV4_ERR_UNSUPPORTED;
+    const long long es = esize(dtype), pix_bytes = (long long)C * es;
+    const long long bytes = (long long)N * H * W * pix_bytes;
+    if (pix_bytes % 16 || bytes >= (1LL << 31))
+        return DCNV4_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(x) & 15u) || (reinterpret_cast<uintptr_t>(w) & 15u) ||
+        (reinterpret_cast<uintptr_t>(y) & 15u) || (reinterpret_cast<uintptr_t>(b) & 15u))
+        return DCNV4_ERR_ALIGN;
+    DwGeo g;
+    g.H = H; g.W = W;
+    g.units = (int)(pix_bytes / 16);
+    g.total = (int)(bytes / 16);
+    g.row_bytes = (int)(W * pix_bytes);
+    g.pix_bytes = (int)pix_bytes;
+    g.div_units = make_div((unsigned)g.units);
+    g.div_w = make_div((unsigned)W);
+    g.div_h = make_div((unsigned)H);
+    const unsigned grid = (unsigned)((g.total + 255) / 256);
+    if (dtype == DCNV4_F16)
+        hipLaunchKernelGGL(dcnv4_depthwise3x3_kernel<_Float16>, dim3(grid), dim3(256), 0, s, (const _Float16 *)x,
+                           (const _Float16 *)w, (const _Float16 *)b, (_Float16 *)y, g);
+    else
+        hipLaunchKernelGGL(dcnv4_depthwise3x3_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)x,
+                           (const float *)w, (const float *)b, (float *)y, g);
+    return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
+}
+
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 }  // namespace
@@ -1637,25 +1672,32 @@ int dcnv4_linear(const void *x, const void *w, const void *b, void *y, long long
     return launch_linear(x, g, dtype, (hipStream_t)stream);
 }
 
-long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int dtype, int lightweight)
+int dcnv4_depthwise3x3(const void *x, const void *w, const void *b, void *y, int N, int H, int W, int C, int dtype,
+                       void *stream)
+{
+    return launch_depthwise(x, w, b, y, N, H, W, C, dtype, (hipStream_t)stream);
+}
+
+long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int dtype, int lightweight, int depthwise)
 {
     if (N < 1 || H < 1 || W < 1 || G < 1 || Cg < 1 || (dtype != DCNV4_F32 && dtype != DCNV4_F16))
         return -1;
     const long long P = (long long)N * H * W, es = esize(dtype), C = (long long)G * Cg;
     const long long om = (long long)align256((size_t)(P * G * 32 * es)), act = (long long)align256((size_t)(P * C * es));
-    return lightweight ? om : om + 2 * act;
+    return om + (lightweight ? 0 : 2 * act) + (depthwise ? act : 0);
 }
 
-int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in, const void *w_om, const void *b_om,
-                         const void *w_out, const void *b_out, void *workspace, long long workspace_bytes, void *y,
-                         int N, int H, int W, int G, int Cg, int kernel_h, int kernel_w, int stride_h, int stride_w,
-                         int pad_h, int pad_w, int dil_h, int dil_w, float offset_scale, int dtype, void *stream)
+int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in, const void *w_dw, const void *b_dw,
+                         const void *w_om, const void *b_om, const void *w_out, const void *b_out, void *workspace,
+                         long long workspace_bytes, void *y, int N, int H, int W, int G, int Cg, int kernel_h,
+                         int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                         float offset_scale, int dtype, void *stream)
 {
     if (!x || !w_om || !workspace || !y)
         return DCNV4_ERR_NULL;
     if ((w_in == nullptr) != (w_out == nullptr))        // the two projections come together (or not at all)
         return DCNV4_ERR_NULL;
-    const bool light = w_in == nullptr;
+    const bool light = w_in == nullptr, dw = w_dw != nullptr;
     Problem q;
     int rc = fill_problem(&q, N, H, W, G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
                           offset_scale, dtype);
@@ -1668,21 +1710,40 @@ int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in, cons
     // the merged layer predicts one set of offsets per INPUT pixel: the window must keep the map's size
     if (q.Ho != H || q.Wo != W || kernel_h != 3)
         return DCNV4_ERR_UNSUPPORTED;
-    const long long need = dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, light ? 1 : 0);
+    const long long need = dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, light ? 1 : 0, dw ? 1 : 0);
     if (workspace_bytes < need)
         return DCNV4_ERR_SHAPE;
     const long long P = (long long)N * H * W, es = esize(dtype);
     const int C = G * Cg;
+    const size_t act = align256((size_t)(P * C * es));
     char *om = (char *)workspace;
-    char *value = om + align256((size_t)(P * G * 32 * es));
-    char *y_op = value + align256((size_t)(P * C * es));
-    // both layers that read x in one pass, then the operator on the merged buffer, then the output layer
-    LinGeo first, last;
+    char *next = om + align256((size_t)(P * G * 32 * es));
+    char *value = nullptr, *y_op = nullptr, *x_dw = nullptr;
+    if (!light) {
+        value = next;
+        y_op = next + act;
+        next += 2 * act;
+    }
+    if (dw)
+        x_dw = next;
+    // Everything that can refuse is checked before the first launch.  Without the depthwise convolution
+    // both layers that read x are one launch; with it the offset/scalar layer reads the convolved map.
+    LinGeo first, second, last;
+    const bool fused = !dw && !light;
     rc = begin_linear(&first, x, P, C, dtype);
     if (!rc && !light)
         rc = add_linear_segment(&first, P, C, dtype, w_in, b_in, value, C);
-    if (!rc)
+    if (!rc && (fused || light) && !dw)
         rc = add_linear_segment(&first, P, C, dtype, w_om, b_om, om, G * 32);
+    if (!rc && dw) {
+        rc = begin_linear(&second, x_dw, P, C, dtype);
+        if (!rc)
+            rc = add_linear_segment(&second, P, C, dtype, w_om, b_om, om, G * 32);
+        if (!rc && ((reinterpret_cast<uintptr_t>(w_dw) & 15u) || (reinterpret_cast<uintptr_t>(b_dw) & 15u)))
+            rc = DCNV4_ERR_ALIGN;
+        if (!rc && (P * C * es >= (1LL << 31) || (C * es) % 16))
+            rc = DCNV4_ERR_UNSUPPORTED;
+    }
     if (!rc && !light) {
         rc = begin_linear(&last, y_op, P, C, dtype);
         if (!rc)
@@ -1691,9 +1752,19 @@ int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in, cons
     if (rc)
         return rc;
     hipStream_t s = (hipStream_t)stream;
-    rc = launch_linear(x, first, dtype, s);
-    if (rc)
-        return rc;
+    if (first.nseg > 0) {
+        rc = launch_linear(x, first, dtype, s);
+        if (rc)
+            return rc;
+    }
+    if (dw) {
+        rc = launch_depthwise(x, w_dw, b_dw, x_dw, N, H, W, C, dtype, s);
+        if (rc)
+            return rc;
+        rc = launch_linear(x_dw, second, dtype, s);
+        if (rc)
+            return rc;
+    }
     rc = forward_impl(light ? x : (const void *)value, om, nullptr, light ? y : (void *)y_op, N, H, W, G, Cg, kernel_h,
                       kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype, stream, true);
     if (rc || light)

@@ -100,14 +100,16 @@ def merge_offset_mask(offset, mask, pad_value=0.0):
     return om
 
 
-def make_module_params(cfg: Config, dtype: str = "f32", seed: int = 0, lightweight: bool = False, pad_value: float = 0.0):
+def make_module_params(cfg: Config, dtype: str = "f32", seed: int = 0, lightweight: bool = False, pad_value: float = 0.0,
+                       depthwise: bool = False):
     """Seeded random weights of the module's linear layers (numpy, `dtype`), sized so that with x ~ N(0,1)
     the predicted offsets have a standard deviation of about cfg.sigma pixels and the modulation scalars
     and projected values of about 1 -- the distributions of the operator-level inputs above:
       w_om [G*27, C] / b_om [G*27]: per group 18 offset rows, then 9 scalar rows (what the single layer
       of the module has); w_om_padded [G*32, C] / b_om_padded [G*32]: the same rows in the 32-entry
       layout, the five padding rows filled with pad_value (their outputs must be ignored);
-      w_in, b_in, w_out, b_out [C, C] / [C] unless lightweight."""
+      w_in, b_in, w_out, b_out [C, C] / [C] unless lightweight; with depthwise also w_dw [3,3,C] ~ N(0, 1/9)
+      (so the convolved map keeps unit variance) and b_dw [C]."""
     gen = torch.Generator(device="cpu")
     gen.manual_seed(seed + 7919)
     C, G = cfg.C, cfg.G
@@ -120,6 +122,9 @@ def make_module_params(cfg: Config, dtype: str = "f32", seed: int = 0, lightweig
         for name in ("in", "out"):
             out["w_" + name] = torch.randn((C, C), generator=gen) / float(np.sqrt(C))
             out["b_" + name] = 0.1 * torch.randn((C,), generator=gen)
+    if depthwise:
+        out["w_dw"] = torch.randn((3, 3, C), generator=gen) / 3.0
+        out["b_dw"] = 0.1 * torch.randn((C,), generator=gen)
     np_dtype = {"f32": np.float32, "f16": np.float16}[dtype]
     out = {k: v.numpy().astype(np_dtype) for k, v in out.items()}
     wp = np.full((G, 32, C), pad_value, dtype=np_dtype)

@@ -102,18 +102,22 @@ def test_linear_and_module_entry_points_validate_on_the_host():
     assert lin(P=1 << 24, K=64) == 3                                 # x of 4 GiB: beyond 32-bit byte offsets
     assert lin(x=A + 8) == 4 and lin(w=A + 4) == 4 and lin(y=A + 2) == 4 and lin(b=A + 2) == 4
 
-    def mod(x=A, w_in=A, w_om=A, w_out=A, ws=A, ws_bytes=1 << 40, y=A, N=1, H=14, W=14, G=4, Cg=16, k=3, s=1, p=1, d=1, dtype=0):
-        return lib.dcnv4_module_forward(x, w_in, None, w_om, None, w_out, None, ws, ws_bytes, y, N, H, W, G, Cg, k, k, s, s, p, p,
-                                        d, d, 1.0, dtype, None)
+    def mod(x=A, w_in=A, w_om=A, w_out=A, w_dw=None, ws=A, ws_bytes=1 << 40, y=A, N=1, H=14, W=14, G=4, Cg=16, k=3, s=1, p=1, d=1, dtype=0):
+        return lib.dcnv4_module_forward(x, w_in, None, w_dw, None, w_om, None, w_out, None, ws, ws_bytes, y, N, H, W, G, Cg, k, k,
+                                        s, s, p, p, d, d, 1.0, dtype, None)
     assert mod(x=None) == 1 and mod(w_om=None) == 1 and mod(ws=None) == 1 and mod(y=None) == 1
     assert mod(w_in=None) == 1 and mod(w_out=None) == 1              # the projections come together
     assert mod(N=0) == 2 and mod(ws_bytes=1000) == 2
     assert mod(p=0) == 3 and mod(s=2) == 3 and mod(k=5, p=2) == 3 and mod(k=1, p=0) == 3 and mod(Cg=12) == 3
     assert mod(G=3, Cg=16) == 3                                      # C = 48: not a multiple of 32 output channels
-    assert mod(ws=A + 8) == 4
+    assert mod(ws=A + 8) == 4 and mod(w_dw=A + 4) == 4
+    dwc = lambda x=A, w=A, b=None, y=A, N=1, H=8, W=8, C=64, dtype=0: lib.dcnv4_depthwise3x3(x, w, b, y, N, H, W, C, dtype, None)
+    assert dwc(x=None) == 1 and dwc(w=None) == 1 and dwc(y=None) == 1 and dwc(H=0) == 2 and dwc(C=6) == 3 and dwc(dtype=3) == 3
+    assert dwc(C=4, dtype=1) == 3 and dwc(N=1 << 12, H=256, W=256, C=64) == 3 and dwc(w=A + 8) == 4 and dwc(b=A + 4) == 4
     P, C, G = 64 * 56 * 56, 128, 8
     assert dcn.dcnv4_module_workspace_bytes(64, 56, 56, G, 16, dcn.DCNV4_F16, True) == 2 * P * G * 32
     assert dcn.dcnv4_module_workspace_bytes(64, 56, 56, G, 16, dcn.DCNV4_F16, False) == 2 * P * (G * 32 + 2 * C)
+    assert dcn.dcnv4_module_workspace_bytes(64, 56, 56, G, 16, dcn.DCNV4_F16, True, True) == 2 * P * (G * 32 + C)
     assert dcn.dcnv4_module_workspace_bytes(0, 56, 56, G, 16, dcn.DCNV4_F16, False) == -1
 
 

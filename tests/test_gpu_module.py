@@ -86,18 +86,20 @@ MODULE_CASES = [Config("m_small", N=2, H=9, W=11, C=64, G=4), Config("m_cg32", N
                 Config("m_wide", N=1, H=7, W=7, C=1024, G=64, sigma=1.0)]
 
 
-def run_module(cfg, dtype, lightweight, seed=0):
+def run_module(cfg, dtype, lightweight, seed=0, depthwise=False):
     x = make_inputs(cfg, dtype, seed=seed)["x"]
-    prm = make_module_params(cfg, dtype, seed=seed, lightweight=lightweight, pad_value=3.0)
+    prm = make_module_params(cfg, dtype, seed=seed, lightweight=lightweight, pad_value=3.0, depthwise=depthwise)
     g = {k: gpu(v, dtype) for k, v in prm.items()}
     out = torch.full(x.shape, 7.0, device="cuda", dtype=TORCH_DT[dtype])
     kw = dict(kernel=cfg.kernel, stride=cfg.stride, pad=cfg.pad, dilation=cfg.dilation, offset_scale=cfg.offset_scale)
     y = dcn.dcnv4_module_forward(gpu(x, dtype), g["w_om_padded"], g["b_om_padded"], cfg.G, w_in=g.get("w_in"),
-                                 b_in=g.get("b_in"), w_out=g.get("w_out"), b_out=g.get("b_out"), out=out, **kw)
+                                 b_in=g.get("b_in"), w_out=g.get("w_out"), b_out=g.get("b_out"), w_dw=g.get("w_dw"),
+                                 b_dw=g.get("b_dw"), out=out, **kw)
     torch.cuda.synchronize()
     ref = oracle.module_forward(x, prm["w_om"], prm["b_om"], cfg.G, w_in=prm.get("w_in"), b_in=prm.get("b_in"),
-                                w_out=prm.get("w_out"), b_out=prm.get("b_out"), storage=NP_DT[dtype], **kw)
-    return close(f"module {cfg.name} {dtype} light={lightweight}", y.cpu().numpy(), ref, MODULE_TOL[dtype], bulk_tol=TOL[dtype])
+                                w_out=prm.get("w_out"), b_out=prm.get("b_out"), w_dw=prm.get("w_dw"), b_dw=prm.get("b_dw"),
+                                storage=NP_DT[dtype], **kw)
+    return close(f"module {cfg.name} {dtype} light={lightweight} dw={depthwise}", y.cpu().numpy(), ref, MODULE_TOL[dtype], bulk_tol=TOL[dtype])
 
 
 @pytest.mark.parametrize("lightweight", [False, True])
@@ -105,6 +107,32 @@ def run_module(cfg, dtype, lightweight, seed=0):
 @pytest.mark.parametrize("cfg", MODULE_CASES, ids=[c.name for c in MODULE_CASES])
 def test_module_forward_matches_oracle(cfg, dtype, lightweight):
     run_module(cfg, dtype, lightweight)
+
+
+@pytest.mark.parametrize("lightweight", [False, True])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("cfg", MODULE_CASES[:4], ids=[c.name for c in MODULE_CASES[:4]])
+def test_module_forward_with_the_depthwise_convolution(cfg, dtype, lightweight):
+    run_module(cfg, dtype, lightweight, depthwise=True)
+
+
+DW_CASES = [(1, 1, 1, 8), (2, 5, 7, 64), (1, 14, 14, 48), (3, 9, 4, 128), (1, 56, 56, 128), (2, 3, 33, 1024)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("N,H,W,C", DW_CASES)
+def test_depthwise_convolution_matches_oracle(N, H, W, C, dtype):
+    rng = np.random.default_rng(N + H * 3 + W * 5 + C)
+    x = rng.standard_normal((N, H, W, C)).astype(NP_DT[dtype])
+    w = (rng.standard_normal((3, 3, C)) / 3.0).astype(NP_DT[dtype])
+    b = rng.standard_normal(C).astype(NP_DT[dtype])
+    out = torch.full((N, H, W, C), 7.0, device="cuda", dtype=TORCH_DT[dtype])
+    y = dcn.dcnv4_depthwise3x3(gpu(x, dtype), gpu(w, dtype), gpu(b, dtype), out=out)
+    torch.cuda.synchronize()
+    close(f"depthwise {N}x{H}x{W}x{C} {dtype}", y.cpu().numpy(), oracle.depthwise3x3(x, w, b), TOL[dtype])
+    y0 = dcn.dcnv4_depthwise3x3(gpu(x, dtype), gpu(w, dtype))
+    torch.cuda.synchronize()
+    close(f"depthwise {N}x{H}x{W}x{C} {dtype} (no bias)", y0.cpu().numpy(), oracle.depthwise3x3(x, w), TOL[dtype])
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
