@@ -58,7 +58,8 @@ enum {
     DCNV4_ERR_SHAPE = 2,       /* a size is non-positive or the window does not fit */
     DCNV4_ERR_UNSUPPORTED = 3, /* kernel size, Cg, dtype or tensor size outside the supported set */
     DCNV4_ERR_ALIGN = 4,       /* a tensor pointer is not 16-byte aligned */
-    DCNV4_ERR_LAUNCH = 5       /* the HIP runtime refused the launch */
+    DCNV4_ERR_LAUNCH = 5,      /* the HIP runtime refused the launch */
+    DCNV4_ERR_TOO_LARGE = 6    /* dcnv4_module_forward_static: the call needs more than the built-in workspace */
 };
 
 /* Output extent of the sliding window: Ho = (H + 2*pad_h - dil_h*(kernel_h-1) - 1)/stride_h + 1,
@@ -189,6 +190,28 @@ int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in,
  * depthwise != 0: with the depthwise convolution); -1 for a bad argument.  Host-only helper. */
 long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int dtype, int lightweight,
                                        int depthwise);
+
+/* dcnv4_module_forward for callers that cannot allocate device memory or hand over a workspace -- code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc: the same kernels, with
+ * the workspace in a buffer built into the library (a static device array of
+ * dcnv4_module_static_workspace_limit() = 32 MiB bytes; every GPU the library runs on holds its own copy
+ * until the process ends).  No allocation of any kind happens in the call.  A call that needs more than the
+ * limit (dcnv4_module_workspace_bytes() tells) returns DCNV4_ERR_TOO_LARGE and does nothing; at 32 MiB
+ * that is e.g. one 200x320x128 fp16 map, or 16 maps of 56x56x128, with both projections.
+ * All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (different streams,
+ * different host threads) race on it; on one stream they are ordered and safe.  Nothing in the buffer
+ * has to start at zero (every tensor in it is written in full before it is read). */
+int dcnv4_module_forward_static(const void *x, const void *w_in, const void *b_in,
+                                const void *w_dw, const void *b_dw,
+                                const void *w_om, const void *b_om,
+                                const void *w_out, const void *b_out, void *y,
+                                int N, int H, int W, int G, int Cg,
+                                int kernel_h, int kernel_w, int stride_h, int stride_w,
+                                int pad_h, int pad_w, int dil_h, int dil_w,
+                                float offset_scale, int dtype, void *stream);
+
+/* Size in bytes of the built-in workspace of dcnv4_module_forward_static.  Host-only helper. */
+long long dcnv4_module_static_workspace_limit(void);
 
 /* Bytes the ideal memory-access model of Sec. 3.2 ("2HWC + 27HWG", every value touched
  * once) assigns to one forward call: x + offset + mask + y.  Host-only helper. */

@@ -18,6 +18,7 @@ EXPORTS = (
     "dcnv4_output_hw", "dcnv4_forward", "dcnv4_backward", "dcnv4_forward_merged", "dcnv4_backward_merged",
     "dcnv4_forward_softmax", "dcnv4_backward_softmax",
     "dcnv4_linear", "dcnv4_depthwise3x3", "dcnv4_module_forward", "dcnv4_module_workspace_bytes",
+    "dcnv4_module_forward_static", "dcnv4_module_static_workspace_limit",
     "dcnv4_forward_algorithmic_bytes", "dcnv4_backward_algorithmic_bytes",
     "dcnv4_forward_merged_algorithmic_bytes", "dcnv4_backward_merged_algorithmic_bytes",
     "dcnv4_set_option", "dcnv4_last_kernel_name", "dcnv4_status_string",
@@ -69,6 +70,10 @@ def load_library():
     lib.dcnv4_depthwise3x3.restype = ci
     lib.dcnv4_module_forward.argtypes = [vp] * 10 + [ctypes.c_longlong, vp] + geo
     lib.dcnv4_module_forward.restype = ci
+    lib.dcnv4_module_forward_static.argtypes = [vp] * 10 + geo
+    lib.dcnv4_module_forward_static.restype = ci
+    lib.dcnv4_module_static_workspace_limit.argtypes = []
+    lib.dcnv4_module_static_workspace_limit.restype = ctypes.c_longlong
     lib.dcnv4_module_workspace_bytes.argtypes = [ci] * 8
     lib.dcnv4_module_workspace_bytes.restype = ctypes.c_longlong
     lib.dcnv4_set_option.argtypes = [ctypes.c_char_p, ci]
@@ -395,4 +400,25 @@ def dcnv4_module_forward(x, w_om, b_om, G, w_in=None, b_in=None, w_out=None, b_o
         rc = load_library().dcnv4_module_forward(*args)
     if rc:
         raise Dcnv4Error(rc, "dcnv4_module_forward")
+    return out
+
+
+def dcnv4_module_static_workspace_limit():
+    return int(load_library().dcnv4_module_static_workspace_limit())
+
+
+def dcnv4_module_forward_static(x, w_om, b_om, G, out, w_in=None, b_in=None, w_out=None, b_out=None, w_dw=None, b_dw=None,
+                                kernel=3, stride=1, pad=1, dilation=1, offset_scale=1.0, stream=None):
+    """dcnv4_module_forward with the workspace in the library's built-in buffer: nothing is allocated, here
+    or in the library (the caller passes `out`).  Raises Dcnv4Error (status 6) if the call needs more than
+    dcnv4_module_static_workspace_limit() bytes."""
+    args = dcnv4_module_forward(x, w_om, b_om, G, w_in=w_in, b_in=b_in, w_out=w_out, b_out=b_out, w_dw=w_dw, b_dw=b_dw,
+                                kernel=kernel, stride=stride, pad=pad, dilation=dilation, offset_scale=offset_scale,
+                                workspace=x, out=out, stream=stream, prepare_only=True)
+    args = args[:9] + args[11:]                      # the same arguments without (workspace, workspace_bytes)
+    import torch
+    with torch.cuda.device(x.device):
+        rc = load_library().dcnv4_module_forward_static(*args)
+    if rc:
+        raise Dcnv4Error(rc, "dcnv4_module_forward_static")
     return out

@@ -1687,11 +1687,34 @@ long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int d
     return om + (lightweight ? 0 : 2 * act) + (depthwise ? act : 0);
 }
 
-int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in, const void *w_dw, const void *b_dw,
-                         const void *w_om, const void *b_om, const void *w_out, const void *b_out, void *workspace,
-                         long long workspace_bytes, void *y, int N, int H, int W, int G, int Cg, int kernel_h,
-                         int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
-                         float offset_scale, int dtype, void *stream)
+namespace {
+
+// Built-in workspace of dcnv4_module_forward_static: one copy per GPU, held until the process ends.
+constexpr long long kScratchBytes = 32ll << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// Device address of `scratch` on the current device (the array's name is only a host-side stand-in:
+// every GPU has its own copy at its own address), looked up once per device; null on failure.
+void *scratch_address()
+{
+    static void *ptr[kMaxDevices];
+    const int dev = current_device();
+    if (dev < 0)
+        return nullptr;
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess)
+            return nullptr;
+        ptr[dev] = p;
+    }
+    return ptr[dev];
+}
+
+int module_forward_impl(const void *x, const void *w_in, const void *b_in, const void *w_dw, const void *b_dw,
+                        const void *w_om, const void *b_om, const void *w_out, const void *b_out, void *workspace,
+                        long long workspace_bytes, void *y, int N, int H, int W, int G, int Cg, int kernel_h,
+                        int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                        float offset_scale, int dtype, void *stream)
 {
     if (!x || !w_om || !workspace || !y)
         return DCNV4_ERR_NULL;
@@ -1772,6 +1795,44 @@ int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in, cons
     return launch_linear(y_op, last, dtype, s);
 }
 
+}  // namespace
+
+int dcnv4_module_forward(const void *x, const void *w_in, const void *b_in, const void *w_dw, const void *b_dw,
+                         const void *w_om, const void *b_om, const void *w_out, const void *b_out, void *workspace,
+                         long long workspace_bytes, void *y, int N, int H, int W, int G, int Cg, int kernel_h,
+                         int kernel_w, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                         float offset_scale, int dtype, void *stream)
+{
+    return module_forward_impl(x, w_in, b_in, w_dw, b_dw, w_om, b_om, w_out, b_out, workspace, workspace_bytes, y, N, H, W,
+                               G, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale,
+                               dtype, stream);
+}
+
+long long dcnv4_module_static_workspace_limit(void) { return kScratchBytes; }
+
+int dcnv4_module_forward_static(const void *x, const void *w_in, const void *b_in, const void *w_dw, const void *b_dw,
+                                const void *w_om, const void *b_om, const void *w_out, const void *b_out, void *y,
+                                int N, int H, int W, int G, int Cg, int kernel_h, int kernel_w, int stride_h,
+                                int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, float offset_scale, int dtype,
+                                void *stream)
+{
+    if (!x || !w_om || !y)
+        return DCNV4_ERR_NULL;
+    if ((w_in == nullptr) != (w_out == nullptr))
+        return DCNV4_ERR_NULL;
+    const long long need = dcnv4_module_workspace_bytes(N, H, W, G, Cg, dtype, w_in == nullptr, w_dw != nullptr);
+    if (need < 0)
+        return (dtype != DCNV4_F32 && dtype != DCNV4_F16) ? DCNV4_ERR_UNSUPPORTED : DCNV4_ERR_SHAPE;
+    if (need > kScratchBytes)
+        return DCNV4_ERR_TOO_LARGE;
+    void *ws = scratch_address();
+    if (!ws)
+        return DCNV4_ERR_LAUNCH;
+    return module_forward_impl(x, w_in, b_in, w_dw, b_dw, w_om, b_om, w_out, b_out, ws, kScratchBytes, y, N, H, W, G, Cg,
+                               kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype,
+                               stream);
+}
+
 int dcnv4_set_option(const char *key, int value)
 {
     if (!key)
@@ -1846,6 +1907,7 @@ const char *dcnv4_status_string(int status)
     case DCNV4_ERR_UNSUPPORTED: return "unsupported kernel size, group width, dtype, option or tensor size";
     case DCNV4_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
     case DCNV4_ERR_LAUNCH: return "HIP launch failed";
+    case DCNV4_ERR_TOO_LARGE: return "the call needs more workspace than the built-in scratch buffer holds";
     }
     return "unknown status";
 }

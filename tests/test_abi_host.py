@@ -111,6 +111,14 @@ def test_linear_and_module_entry_points_validate_on_the_host():
     assert mod(p=0) == 3 and mod(s=2) == 3 and mod(k=5, p=2) == 3 and mod(k=1, p=0) == 3 and mod(Cg=12) == 3
     assert mod(G=3, Cg=16) == 3                                      # C = 48: not a multiple of 32 output channels
     assert mod(ws=A + 8) == 4 and mod(w_dw=A + 4) == 4
+
+    def mod_static(x=A, w_in=A, w_om=A, w_out=A, y=A, N=1, H=14, W=14, G=4, Cg=16, dtype=0):
+        return lib.dcnv4_module_forward_static(x, w_in, None, None, None, w_om, None, w_out, None, y, N, H, W, G, Cg, 3, 3,
+                                               1, 1, 1, 1, 1, 1, 1.0, dtype, None)
+    assert mod_static(x=None) == 1 and mod_static(w_om=None) == 1 and mod_static(y=None) == 1 and mod_static(w_in=None) == 1
+    assert mod_static(N=0) == 2 and mod_static(dtype=2) == 3
+    assert mod_static(N=64, H=56, W=56, G=8) == 6                    # more workspace than the built-in buffer holds
+    assert dcn.dcnv4_module_static_workspace_limit() == 32 << 20 and "scratch" in dcn.dcnv4_status_string(6)
     dwc = lambda x=A, w=A, b=None, y=A, N=1, H=8, W=8, C=64, dtype=0: lib.dcnv4_depthwise3x3(x, w, b, y, N, H, W, C, dtype, None)
     assert dwc(x=None) == 1 and dwc(w=None) == 1 and dwc(y=None) == 1 and dwc(H=0) == 2 and dwc(C=6) == 3 and dwc(dtype=3) == 3
     assert dwc(C=4, dtype=1) == 3 and dwc(N=1 << 12, H=256, W=256, C=64) == 3 and dwc(w=A + 8) == 4 and dwc(b=A + 4) == 4
