@@ -53,3 +53,31 @@ def test_static_workspace_module_forward_refuses_what_does_not_fit():
     assert e.value.status == 6 and "scratch" in str(e.value)
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+def test_static_workspace_module_forward_replays_from_a_hip_graph():
+    """What the entry point is for: under capture nothing may allocate.  (The first call on a device, which
+    looks the buffer's address up, is made before the capture.)  Every replay, with new input values in the
+    same buffers and eager work in between, must equal the eager call with a caller-owned workspace."""
+    cfg = Config("na_graph", N=1, H=20, W=24, C=64, G=4)
+    prm = {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in make_module_params(cfg, "f16", seed=5).items()}
+    kw = dict(w_in=prm["w_in"], b_in=prm["b_in"], w_out=prm["w_out"], b_out=prm["b_out"])
+    x = torch.from_numpy(make_inputs(cfg, "f16", seed=5)["x"]).cuda()
+    out = torch.empty_like(x)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        dcn.dcnv4_module_forward_static(x, prm["w_om_padded"], prm["b_om_padded"], cfg.G, out, stream=s, **kw)
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        dcn.dcnv4_module_forward_static(x, prm["w_om_padded"], prm["b_om_padded"], cfg.G, out, stream=s, **kw)
+    for rep in range(3):
+        x.copy_(torch.from_numpy(make_inputs(cfg, "f16", seed=50 + rep)["x"]))
+        out.fill_(3.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ref = dcn.dcnv4_module_forward(x, prm["w_om_padded"], prm["b_om_padded"], cfg.G, **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), rep
