@@ -242,7 +242,7 @@ long long dcnv4_backward_merged_algorithmic_bytes(int N, int H, int W, int G, in
  *   "fwd_single"  LDS rectangle buffers of the staged gather kernels: 1 = always two (the next tile
  *                 streams in during the current one), 2 = always one (bigger rectangle, refilled
  *                 between tiles), 0 = whichever the tile chooser estimates to be cheaper
- *   "wg_per_cu"   persistent workgroups per compute unit of the rectangle kernels (1..16, as far as
+ *   "wg_per_cu"   persistent workgroups per compute unit of the rectangle kernels (1..32, as far as
  *                 LDS allows)
  *   "gom_coop"    1 = the fp32 grad_offset/grad_mask pass moves its values through per-wave LDS slices
  *                 even for whole groups (default: each lane reads and writes its own pixel's values)

@@ -513,7 +513,7 @@ struct Options {
     int halo = 0;          // displacement in pixels (rows, for the ring) the staged window allows for
     int lds_kb = 0;        // LDS budget per workgroup of the staged kernels (8..160)
     int fwd_threads = 0;   // workgroup size of the staged forward kernels (64, 128, 256, 512, 640, 768)
-    int wg_per_cu = 0;     // persistent workgroups per compute unit of the rectangle kernels (1..16)
+    int wg_per_cu = 0;     // persistent workgroups per compute unit of the rectangle kernels (1..32)
     int fwd_single = 0;    // rectangle buffers of the staged gather kernels: 1 always two, 2 always one
     int gx_threads = 0;    // workgroup size of the grad_x kernel (256, 512, 768)
     int gom_coop = 0;      // 1: the fp32 grad_offset/grad_mask pass goes through LDS slices even for whole groups
@@ -931,7 +931,7 @@ int prepare_tiled(const Problem &q, bool any_tile_size, int want_nbuf, int want_
         return DCNV4_ERR_LAUNCH;
     // several persistent workgroups per compute unit when their LDS and registers fit: their tile
     // switches (barrier, drained pipeline) then overlap with each other's work
-    int per_cu = g_opt.wg_per_cu ? g_opt.wg_per_cu : want_per_cu ? want_per_cu : (MODE != kTiledFwd || CG * sizeof(T) >= 64 ? 1 : THREADS == 256 ? 2 : THREADS == 64 ? 8 : 1);
+    int per_cu = g_opt.wg_per_cu ? g_opt.wg_per_cu : want_per_cu ? want_per_cu : (MODE != kTiledFwd || CG * sizeof(T) >= 64 ? 1 : THREADS == 256 ? 2 : THREADS == 64 ? 16 : 1);
     while (per_cu > 1 && (per_cu * lds > kMaxLdsBytes || per_cu * THREADS > 2048))
         --per_cu;
     const int slots = cus * per_cu;
@@ -1869,7 +1869,7 @@ int dcnv4_set_option(const char *key, int value)
         g_opt.gom_coop = value;
         return DCNV4_OK;
     }
-    if (!strcmp(key, "wg_per_cu") && value >= 0 && value <= 16) {
+    if (!strcmp(key, "wg_per_cu") && value >= 0 && value <= 32) {
         g_opt.wg_per_cu = value;
         return DCNV4_OK;
     }

@@ -131,7 +131,7 @@ def test_linear_and_module_entry_points_validate_on_the_host():
 
 def test_options():
     assert dcn.dcnv4_last_kernel_name(0) is None or dcn.dcnv4_last_kernel_name(0).startswith("dcnv4_fwd")
-    for key, bad in (("fwd_cpt", 5), ("nonsense", 1), ("fwd_path", 4), ("bwd_path", 3), ("fwd_single", 3), ("wg_per_cu", 17), ("halo", 65), ("lds_kb", 4), ("fwd_threads", 100)):
+    for key, bad in (("fwd_cpt", 5), ("nonsense", 1), ("fwd_path", 4), ("bwd_path", 3), ("fwd_single", 3), ("wg_per_cu", 33), ("halo", 65), ("lds_kb", 4), ("fwd_threads", 100)):
         with pytest.raises(dcn.Dcnv4Error):
             dcn.dcnv4_set_option(key, bad)
     for key, ok in (("fwd_cpt", 8), ("fwd_path", 2), ("bwd_path", 2), ("halo", 10), ("lds_kb", 64), ("fwd_threads", 512), ("fwd_threads", 128), ("bwd_cpt", 4)):
