@@ -200,7 +200,8 @@ long long dcnv4_module_workspace_bytes(int N, int H, int W, int G, int Cg, int d
  * that is e.g. one 200x320x128 fp16 map, or 16 maps of 56x56x128, with both projections.
  * All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (different streams,
  * different host threads) race on it; on one stream they are ordered and safe.  Nothing in the buffer
- * has to start at zero (every tensor in it is written in full before it is read). */
+ * has to start at zero (every tensor in it is written in full before it is read).  The first call on a
+ * device looks the buffer's address up (hipGetSymbolAddress): make one call before capturing a graph. */
 int dcnv4_module_forward_static(const void *x, const void *w_in, const void *b_in,
                                 const void *w_dw, const void *b_dw,
                                 const void *w_om, const void *b_om,
