@@ -245,6 +245,8 @@ long long dcnv4_backward_merged_algorithmic_bytes(int N, int H, int W, int G, in
  *                 between tiles), 0 = whichever the tile chooser estimates to be cheaper
  *   "wg_per_cu"   persistent workgroups per compute unit of the rectangle kernels (1..32, as far as
  *                 LDS allows)
+ *   "module_rows" 1 = dcnv4_module_forward keeps the tensors between its layers channel-last (default: the
+ *                 full module keeps them plane-major, one (image, group) after the other)
  *   "gom_coop"    1 = the fp32 grad_offset/grad_mask pass moves its values through per-wave LDS slices
  *                 even for whole groups (default: each lane reads and writes its own pixel's values)
  *   "gx_threads"  workgroup size of the staged grad_x kernel (256, 512 or 768)

@@ -517,6 +517,7 @@ struct Options {
     int fwd_single = 0;    // rectangle buffers of the staged gather kernels: 1 always two, 2 always one
     int gx_threads = 0;    // workgroup size of the grad_x kernel (256, 512, 768)
     int gom_coop = 0;      // 1: the fp32 grad_offset/grad_mask pass goes through LDS slices even for whole groups
+    int module_rows = 0;   // 1: the module keeps its tensors channel-last between the layers (default: plane-major)
 } g_opt;
 
 char g_last_kernel[2][96];
@@ -1474,7 +1475,8 @@ int backward_impl(const void *x, const void *offset, const void *mask, const voi
 // ---- the module's linear layers ----------------------------------------------------------------
 // One layer of the linear kernel's work list, checked: K * element size a multiple of 32 bytes (one
 // MFMA group), nout a multiple of 32 (one MFMA block), 32-bit byte offsets inside every tensor.
-int add_linear_segment(LinGeo *g, long long P, int K, int dtype, const void *w, const void *b, void *y, int nout)
+int add_linear_segment(LinGeo *g, long long P, int K, int dtype, const void *w, const void *b, void *y, int nout,
+                       int plane_shift = 0)
 {
     if (!w || !y)
         return DCNV4_ERR_NULL;
@@ -1488,6 +1490,7 @@ int add_linear_segment(LinGeo *g, long long P, int K, int dtype, const void *w, 
         return DCNV4_ERR_ALIGN;
     LinSeg &sg = g->seg[g->nseg++];
     sg.w = w; sg.b = b; sg.y = y; sg.nout = nout;
+    sg.plane_shift = plane_shift;
     sg.nblocks = (nout + kLinBlock - 1) / kLinBlock;
     return DCNV4_OK;
 }
@@ -1749,19 +1752,36 @@ int module_forward_impl(const void *x, const void *w_in, const void *b_in, const
     }
     if (dw)
         x_dw = next;
+    // Between its layers the full module keeps value, offsets/scalars and the operator's output plane-major,
+    // [image][group][pixel][channels of the group]: the operator then sees N*G images of ONE group whose
+    // pixels are whole, contiguous pieces (a workgroup of its kernels reads full cache lines instead of a
+    // quarter of each), and the linear layers write and read 1 KB runs.  (Not the lightweight variant, whose
+    // value tensor is the caller's channel-last x; not groups whose bytes are no power of two in 32..128.)
+    int vshift = 0;
+    for (int sft = 5; sft <= 7; ++sft)
+        if ((long long)Cg * es == (1LL << sft))
+            vshift = sft;
+    const bool planar = !light && vshift != 0 && g_opt.module_rows == 0;
+    const int oshift = planar ? (es == 2 ? 6 : 7) : 0;            // 32 entries per (pixel, group)
+    if (!planar)
+        vshift = 0;
     // Everything that can refuse is checked before the first launch.  Without the depthwise convolution
     // both layers that read x are one launch; with it the offset/scalar layer reads the convolved map.
     LinGeo first, second, last;
     const bool fused = !dw && !light;
     rc = begin_linear(&first, x, P, C, dtype);
     if (!rc && !light)
-        rc = add_linear_segment(&first, P, C, dtype, w_in, b_in, value, C);
+        rc = add_linear_segment(&first, P, C, dtype, w_in, b_in, value, C, vshift);
     if (!rc && (fused || light) && !dw)
-        rc = add_linear_segment(&first, P, C, dtype, w_om, b_om, om, G * 32);
+        rc = add_linear_segment(&first, P, C, dtype, w_om, b_om, om, G * 32, oshift);
+    first.hw = H * W;
+    first.div_hw = make_div((unsigned)(H * W));
     if (!rc && dw) {
         rc = begin_linear(&second, x_dw, P, C, dtype);
         if (!rc)
-            rc = add_linear_segment(&second, P, C, dtype, w_om, b_om, om, G * 32);
+            rc = add_linear_segment(&second, P, C, dtype, w_om, b_om, om, G * 32, oshift);
+        second.hw = H * W;
+        second.div_hw = make_div((unsigned)(H * W));
         if (!rc && ((reinterpret_cast<uintptr_t>(w_dw) & 15u) || (reinterpret_cast<uintptr_t>(b_dw) & 15u)))
             rc = DCNV4_ERR_ALIGN;
         if (!rc && (P * C * es >= (1LL << 31) || (C * es) % 16))
@@ -1771,6 +1791,9 @@ int module_forward_impl(const void *x, const void *w_in, const void *b_in, const
         rc = begin_linear(&last, y_op, P, C, dtype);
         if (!rc)
             rc = add_linear_segment(&last, P, C, dtype, w_out, b_out, y, C);
+        last.hw = H * W;
+        last.div_hw = make_div((unsigned)(H * W));
+        last.in_plane_shift = vshift;
     }
     if (rc)
         return rc;
@@ -1788,8 +1811,12 @@ int module_forward_impl(const void *x, const void *w_in, const void *b_in, const
         if (rc)
             return rc;
     }
-    rc = forward_impl(light ? x : (const void *)value, om, nullptr, light ? y : (void *)y_op, N, H, W, G, Cg, kernel_h,
-                      kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype, stream, true);
+    if (planar)
+        rc = forward_impl(value, om, nullptr, y_op, N * G, H, W, 1, Cg, kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w,
+                          dil_h, dil_w, offset_scale, dtype, stream, true);
+    else
+        rc = forward_impl(light ? x : (const void *)value, om, nullptr, light ? y : (void *)y_op, N, H, W, G, Cg, kernel_h,
+                          kernel_w, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, offset_scale, dtype, stream, true);
     if (rc || light)
         return rc;
     return launch_linear(y_op, last, dtype, s);
@@ -1863,6 +1890,10 @@ int dcnv4_set_option(const char *key, int value)
     }
     if (!strcmp(key, "fwd_single") && value >= 0 && value <= 2) {
         g_opt.fwd_single = value;
+        return DCNV4_OK;
+    }
+    if (!strcmp(key, "module_rows") && (value == 0 || value == 1)) {
+        g_opt.module_rows = value;
         return DCNV4_OK;
     }
     if (!strcmp(key, "gom_coop") && (value == 0 || value == 1)) {

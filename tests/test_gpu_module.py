@@ -83,7 +83,8 @@ def test_linear_layer_on_an_nhwc_map_and_its_refusals():
 
 MODULE_CASES = [Config("m_small", N=2, H=9, W=11, C=64, G=4), Config("m_cg32", N=1, H=12, W=10, C=128, G=4),
                 Config("m_ring", N=2, H=24, W=30, C=32, G=2), Config("m_dil", N=1, H=14, W=13, C=96, G=6, pad=2, dilation=2),
-                Config("m_wide", N=1, H=7, W=7, C=1024, G=64, sigma=1.0)]
+                Config("m_wide", N=1, H=7, W=7, C=1024, G=64, sigma=1.0), Config("m_cg8", N=3, H=6, W=7, C=32, G=4),
+                Config("m_cg64", N=3, H=10, W=9, C=128, G=2)]
 
 
 def run_module(cfg, dtype, lightweight, seed=0, depthwise=False):
@@ -133,6 +134,18 @@ def test_depthwise_convolution_matches_oracle(N, H, W, C, dtype):
     y0 = dcn.dcnv4_depthwise3x3(gpu(x, dtype), gpu(w, dtype))
     torch.cuda.synchronize()
     close(f"depthwise {N}x{H}x{W}x{C} {dtype} (no bias)", y0.cpu().numpy(), oracle.depthwise3x3(x, w), TOL[dtype])
+
+
+@pytest.mark.parametrize("depthwise", [False, True])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("cfg", MODULE_CASES, ids=[c.name for c in MODULE_CASES])
+def test_module_forward_with_channel_last_tensors_between_the_layers(cfg, dtype, depthwise):
+    """By default the full module keeps its intermediate tensors plane-major (one (image, group) after the
+    other); the switch "module_rows" keeps them channel-last.  Both must match the oracle."""
+    if depthwise and cfg.name == "m_wide":
+        pytest.skip("covered without the depthwise convolution")
+    dcn.dcnv4_set_option("module_rows", 1)
+    run_module(cfg, dtype, lightweight=False, depthwise=depthwise)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
