@@ -1152,7 +1152,7 @@ int make_rgeo(const Problem &q, int waves, int grid_wgs, RGeo *out)
     return DCNV4_OK;
 }
 
-template <int WAVES>
+template <int WAVES, bool SOFTMAX = false>
 int launch_ring_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
     const int cus = device_cus();
@@ -1174,19 +1174,21 @@ int launch_ring_fwd(const void *x, const void *off, const void *msk, void *y, co
     const int lds = p.ring * p.pitch * kRingRecBytes + 128;
     if (lds > kMaxLdsBytes)
         return DCNV4_ERR_UNSUPPORTED;
-    auto kern = dcnv4_ring_fwd_kernel<WAVES>;
+    auto kern = dcnv4_ring_fwd_kernel<WAVES, SOFTMAX>;
     static int granted[kMaxDevices];
     if (!grant_lds(reinterpret_cast<const void *>(kern), lds, granted))
         return DCNV4_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), lds, s, (const _Float16 *)x, (const _Float16 *)off,
                        (const _Float16 *)msk, (_Float16 *)y, p);
-    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), "dcnv4_ring_fwd_kernel<%d>", WAVES);
+    snprintf(g_last_kernel[0], sizeof(g_last_kernel[0]), SOFTMAX ? "dcnv4_ring_fwd_kernel<%d, softmax>" : "dcnv4_ring_fwd_kernel<%d>", WAVES);
     return hipGetLastError() == hipSuccess ? DCNV4_OK : DCNV4_ERR_LAUNCH;
 }
 
 int dispatch_ring_fwd(const void *x, const void *off, const void *msk, void *y, const Problem &q, hipStream_t s)
 {
     // eight waves: two per SIMD, 256 registers each (four waves on request, for tests)
+    if (q.softmax)
+        return g_opt.fwd_threads == 256 ? launch_ring_fwd<4, true>(x, off, msk, y, q, s) : launch_ring_fwd<8, true>(x, off, msk, y, q, s);
     if (g_opt.fwd_threads == 256)
         return launch_ring_fwd<4>(x, off, msk, y, q, s);
     return launch_ring_fwd<8>(x, off, msk, y, q, s);
@@ -1202,7 +1204,7 @@ int dispatch_fwd(const void *x, const void *off, const void *msk, void *y, const
     }
     // (maps of a few batches per image leave most of a ring workgroup idle: the rectangle kernels,
     // with several small workgroups per compute unit, are faster there -- measured at 14x14 and 7x7)
-    if (sizeof(T) == 2 && !q.softmax && (g_opt.fwd_path == 3 || (g_opt.fwd_path == 0 && q.Ho * q.Wo >= 512))) {
+    if (sizeof(T) == 2 && (g_opt.fwd_path == 3 || (g_opt.fwd_path == 0 && q.Ho * q.Wo >= 512))) {
         const int rc = dispatch_ring_fwd(x, off, msk, y, q, s);
         if (rc != DCNV4_ERR_UNSUPPORTED || g_opt.fwd_path == 3)
             return rc;

@@ -176,6 +176,21 @@ def test_softmax_form_geometries(cfg, dtype, opts):
     check_softmax(cfg, dtype, seed=51, backward=not (dtype == "f16" and cfg.Cg == 64))
 
 
+RING_SOFTMAX = [Config("rs_big", N=2, H=24, W=30, C=32, G=2), Config("rs_far", N=1, H=40, W=36, C=48, G=3, sigma=7.0),
+                Config("rs_s2", N=2, H=47, W=45, C=16, G=1, stride=2, pad=2, dilation=2)]
+
+
+@pytest.mark.parametrize("cfg", RING_SOFTMAX, ids=[c.name for c in RING_SOFTMAX])
+@pytest.mark.parametrize("opts", [{"fwd_path": 3}, {"fwd_path": 3, "halo": 2}], ids=["ring", "ring_small_halo"])
+def test_softmax_form_through_the_ring_forward(cfg, opts):
+    """fp16, groups of 16: the forward out of the ring of rows normalises the logits in registers too, also
+    for the taps that leave the ring and are redone from memory (large offsets, small halo)."""
+    for k, v in opts.items():
+        dcn.dcnv4_set_option(k, v)
+    check_softmax(cfg, "f16", seed=52, backward=False)
+    assert dcn.dcnv4_last_kernel_name(0).startswith("dcnv4_ring_fwd_kernel")
+
+
 # ------------------------------------------------------------------ windows other than 3x3
 WINDOWS = [Config("k1", N=2, H=9, W=11, C=48, G=3, kernel=1, pad=0), Config("k1_cg8", N=1, H=7, W=7, C=16, G=2, kernel=1, pad=0),
            Config("k1_s2", N=2, H=12, W=10, C=64, G=2, kernel=1, pad=1, stride=2),
