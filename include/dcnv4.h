@@ -124,7 +124,8 @@ int dcnv4_backward_merged(const void *x, const void *offset_mask, const void *gr
  * softmax-normalised; DCNv4 removes exactly this): `mask_logits` [N,Ho,Wo,G,9] holds logits, and
  * m = softmax over the 9 taps is formed inside the kernels, in registers, before the aggregation
  * (expf of the shifted logits in fp32).  Everything else as in dcnv4_forward.  Runs through the
- * input-rectangle kernels only; a shape they do not take is refused with DCNV4_ERR_UNSUPPORTED. */
+ * LDS-staged kernels only (ring of rows or input rectangle); a shape they do not take is refused with
+ * DCNV4_ERR_UNSUPPORTED. */
 int dcnv4_forward_softmax(const void *x, const void *offset, const void *mask_logits, void *y,
                           int N, int H, int W, int G, int Cg,
                           int kernel_h, int kernel_w, int stride_h, int stride_w,
