@@ -25,7 +25,9 @@
  * with (Ho, Wo) as returned by dcnv4_output_hw().  The library allocates nothing and
  * keeps nothing between calls except the test switches below; it enqueues its kernels
  * on `stream` (a hipStream_t, NULL = the default stream) and returns without
- * synchronising.  Outputs must not alias inputs.
+ * synchronising.  Outputs must not alias inputs.  (The module entry points further down
+ * need memory for the tensors between their layers: dcnv4_module_forward takes it from the
+ * caller, dcnv4_module_forward_static from a 32 MiB device array that is part of the library.)
  *
  * Supported: square windows of 3x3 (every entry point and kernel), 1x1 and 5x5 (dcnv4_forward in
  * F32 and F16, dcnv4_backward in F32, through the direct kernels; 5x5 forward needs Cg >= 16; K = 1 or
@@ -55,7 +57,7 @@ enum { DCNV4_F32 = 0, DCNV4_F16 = 1 };
 enum {
     DCNV4_OK = 0,
     DCNV4_ERR_NULL = 1,        /* a required pointer is NULL */
-    DCNV4_ERR_SHAPE = 2,       /* a size is non-positive or the window does not fit */
+    DCNV4_ERR_SHAPE = 2,       /* a size is non-positive, the window does not fit, or a workspace is too small */
     DCNV4_ERR_UNSUPPORTED = 3, /* kernel size, Cg, dtype or tensor size outside the supported set */
     DCNV4_ERR_ALIGN = 4,       /* a tensor pointer is not 16-byte aligned */
     DCNV4_ERR_LAUNCH = 5,      /* the HIP runtime refused the launch */
