@@ -154,6 +154,30 @@ def test_module_forward_at_the_stage1_shape(dtype):
     run_module(CONFIGS["c2"], dtype, lightweight=False)
 
 
+@pytest.mark.parametrize("name", ["paper_28x28x256", "paper_14x14x512", "paper_7x7x1024"])
+@pytest.mark.parametrize("lightweight", [False, True])
+def test_module_forward_at_the_papers_module_benchmark_shapes_fp16(name, lightweight):
+    """Full size (batch 64, 32 channels per group), the shapes of the paper's module-level table."""
+    run_module(CONFIGS[name], "f16", lightweight)
+
+
+def test_linear_layer_on_random_shapes():
+    """Seeded random (P, K, Nout) within the kernel's rules: K * element size a multiple of 32 bytes, Nout of 32."""
+    rng = np.random.default_rng(77)
+    for case in range(24):
+        dtype = "f16" if case % 2 else "f32"
+        kstep = 16 if dtype == "f16" else 8
+        P = int(rng.integers(1, 700))
+        K = int(rng.integers(1, 40)) * kstep
+        Nout = int(rng.integers(1, 14)) * 32
+        x = rng.standard_normal((P, K)).astype(NP_DT[dtype])
+        w = (rng.standard_normal((Nout, K)) / np.sqrt(K)).astype(NP_DT[dtype])
+        b = rng.standard_normal(Nout).astype(NP_DT[dtype]) if case % 3 else None
+        y = dcn.dcnv4_linear(gpu(x, dtype), gpu(w, dtype), gpu(b, dtype))
+        torch.cuda.synchronize()
+        close(f"linear case {case}: {P}x{K}->{Nout} {dtype}", y.cpu().numpy(), oracle.linear(x, w, b), TOL[dtype])
+
+
 def test_module_refusals_leave_y_untouched():
     cfg = Config("m_bad", N=1, H=8, W=8, C=64, G=4)
     x = gpu(make_inputs(cfg, "f32")["x"], "f32")
