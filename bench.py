@@ -363,6 +363,19 @@ def main():
                 "sample": f"one forward pass over the first {n1} of {cfg.N} images ({dt1:.1f} s)"}
         except OSError:
             pass
+        # the oracle's backward on the same shape in fp32 (one pass over the whole batch: well under a second)
+        try:
+            from paper_2401_06197_amd.synth import make_inputs
+            nb = cfg.N
+            tb = {k: v[:nb] for k, v in make_inputs(cfg, "f32", seed=0).items()}
+            t0 = time.perf_counter()
+            oracle.backward(tb["x"], tb["offset"], tb["mask"], tb["grad_y"], **geo)
+            dtb = time.perf_counter() - t0
+            rec["cpu_baseline"]["backward"] = {
+                "value": (out_elems // cfg.N) * nb / dtb, "unit": "output elems/s", "cores": oracle.threads(), "kind": "oracle",
+                "sample": f"one backward pass (grad_x, grad_offset, grad_mask; double precision) over the first {nb} of {cfg.N} images ({dtb:.1f} s)"}
+        except MemoryError:
+            pass
         if head_y is not None:
             err = np.abs(head_y - ref)
             tol = 2e-2 if head.endswith("f16") else 1e-5
